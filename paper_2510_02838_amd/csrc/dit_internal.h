@@ -1,0 +1,102 @@
+// Internal declarations shared by the host runtime and the kernel translation units.
+// Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace dit {
+
+typedef uint16_t bf16_t;  // storage type of bf16 tensors
+
+// ---- GEMM ---------------------------------------------------------------------------
+enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_GELU_BF16 = 2, OUT_RESID_F32 = 3 };
+
+struct GemmProblem {
+  const bf16_t* A; int lda;     // [M][lda] activations
+  const bf16_t* W; int ldw;     // [N_pad][ldw] weights, out-major
+  const float* bias;            // [N] or null
+  int M, N, K;
+  int out_kind; void* out; int ldc;
+  const float* gate; int gate_stride; const int* row_req;  // OUT_RESID_F32 only
+  int tiles_m, tiles_n, tile_start;                        // filled by the launcher
+};
+struct GemmBatch { int n; int total_tiles; GemmProblem p[3]; };
+
+// Launches up to 3 independent problems in one grid.  Returns the tile shape used (BM*1000+BN).
+int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile = 0);
+
+// ---- attention ----------------------------------------------------------------------
+struct AttnTile { int seg; int q0; };   // one block of 128 queries of one segment
+struct AttnArgs {
+  const bf16_t* q; int ldq;
+  const bf16_t* k; int ldk;
+  const bf16_t* vt; int ldvt;   // [H][dh][ldvt]
+  bf16_t* o; int ldo;
+  int n_heads, head_dim;
+  const int* cu_q; const int* cu_k; const int* vt_off;   // device
+  const AttnTile* tiles; int n_tiles;                    // device
+  // optional scatter of output rows: row j of segment s goes to o_row = map(...)
+  const int* o_row_map;         // device [Nq] or null (identity)
+  float scale_log2;             // log2(e)/sqrt(dh)
+};
+void launch_attention(hipStream_t s, const AttnArgs& a);
+
+// ---- row-wise / elementwise ---------------------------------------------------------
+void launch_ln_modulate(hipStream_t s, const float* x, bf16_t* y, int M, int d,
+                        const float* shift, const float* scale, int mod_stride,
+                        const int* row_req, const float* gain, const float* beta);
+
+// q/k per-head RMS norm (+ rotary) from a [M][ld] bf16 matrix holding q at column 0, k at
+// column d; writes rows to qo/ko at row dst_row[m] (or m).  rope: [n_dst_rows][dh/2] (cos,sin)
+// indexed by destination row, or null.
+void launch_qknorm_rope(hipStream_t s, const bf16_t* qkv, int ld, int M, int H, int dh,
+                        const float* qgain, const float* kgain, const float2* rope,
+                        const int* dst_row, bf16_t* qo, bf16_t* ko, int ldo, int k_col_off,
+                        int do_k);
+
+// V transpose: v rows [M][ld] at column v_col_off (+h*dh) -> vt[h][c][col], col = vt_col[m].
+// Tiles of 64 destination columns; tile t covers columns 64t..64t+63 and takes source
+// rows src_of_col[col] (-1 = write zero).
+void launch_v_transpose(hipStream_t s, const bf16_t* v, int ld, int v_col_off, int H, int dh,
+                        const int* src_of_col, int n_cols_pad, bf16_t* vt, int ldvt);
+
+void launch_latent_update(hipStream_t s, float* x, const float* v, long long n, float a, float b);
+
+// y[m][n] = sum_k f(x[m][k]) W[n][k] + b[n] (+ add[(m % add_mod)][n]); f = SiLU if silu_in.
+// x fp32 [M][ldx], W bf16 [N][ldw], y fp32 [M][ldy].
+void launch_skinny(hipStream_t s, const float* x, int ldx, const bf16_t* W, int ldw,
+                   const float* bias, float* y, int ldy, int M, int N, int K, int silu_in);
+
+void launch_timestep_features(hipStream_t s, const float* sigma_dev, float* out, int M);
+
+// patchify: latents fp32 packed -> bf16 [n_img][ldp] (columns >= pdim zero)
+struct TokInfo { int req; int f, i, j; };  // per image token: request and grid position
+void launch_patchify(hipStream_t s, const float* lat, const long long* lat_off_dev,
+                     const int4* req_dims_dev /* (F,H,W,unused) per req */,
+                     const TokInfo* tok, int n_img, int C, int pt, int ph, int pw,
+                     bf16_t* out, int ldp);
+// x[m][c] += PE(i,j)[c] for family J
+void launch_add_pe(hipStream_t s, float* x, const TokInfo* tok, int n_img, int d);
+// unpatchify + update: for every latent element: v = y[token][feat]; x = a x + b v
+void launch_unpatchify_update(hipStream_t s, float* lat, float* v_out, const float* y, int ldy,
+                              const long long* lat_off_dev, const int4* req_dims_dev,
+                              const int* img_off_dev, const float* a_dev, const float* b_dev,
+                              int n_req, long long total, int C, int pt, int ph, int pw);
+// rope table: out[row][j] = (cos, sin) of pos-dependent angle; rows with tok_of_row < 0 get (1,0)
+void launch_rope_table(hipStream_t s, const TokInfo* tok, const int* tok_of_row, int n_rows,
+                       int dh, int ax0, int ax1, int ax2, float theta, float2* out);
+// out[m][:] = table[(m % 1)...] helpers for family W: e[r][6d] = base[r][6d] + table[6d]
+void launch_add_rows(hipStream_t s, const float* base, int ld_base, const float* table,
+                     float* out, int ld_out, int M, int N);
+// gather rows: dst[dst_row[m]] = src[m] (fp32, d columns); either map may be null
+void launch_copy_rows_f32(hipStream_t s, const float* src, const int* src_row, float* dst,
+                          const int* dst_row, int M, int d);
+
+// weights
+void launch_init_matrix(hipStream_t s, bf16_t* w, int rows_out, int cols_in, int ldw,
+                        uint64_t key, float std);   // element (o,i) from logical index i*rows_out+o
+void launch_init_table_f32(hipStream_t s, float* w, long long n, uint64_t key, float std);
+void launch_fill_f32(hipStream_t s, float* p, long long n, float v);
+void launch_fill_u16(hipStream_t s, bf16_t* p, long long n, uint16_t v);
+
+}  // namespace dit

@@ -1,0 +1,460 @@
+// HBM-bound kernels of the denoising step: adaLN layer norm + modulation, per-head q/k RMS
+// norm + rotary code, V transpose, patchify / unpatchify + latent update, the small-M
+// matrix-vector products of the conditioning path, and weight initialisation.
+// All of them are coalesced row-wise kernels with wavefront (64-lane) reductions.
+#include "dit_internal.h"
+
+namespace dit {
+
+__device__ __forceinline__ uint16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf2f(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+__device__ __forceinline__ uint32_t pack2(float a, float b) { return (uint32_t)f2bf(a) | ((uint32_t)f2bf(b) << 16); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------
+// adaLN:  y = LN(x) * (1 + scale[req]) + shift[req]        (or LN(x) * gain + beta)
+// one wave per row; the row lives in registers between the two passes (mean, variance).
+// ---------------------------------------------------------------------------------------
+template <int MAXV>
+__global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restrict__ x, bf16_t* __restrict__ y,
+                                                          int M, int d, const float* __restrict__ shift,
+                                                          const float* __restrict__ scale, int mod_stride,
+                                                          const int* __restrict__ row_req,
+                                                          const float* __restrict__ gain,
+                                                          const float* __restrict__ beta) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= M) return;
+  const int lane = threadIdx.x & 63;
+  const int nv = d >> 8;                       // float4 vectors per lane
+  const float4* xr = (const float4*)(x + (size_t)row * d);
+  float4 v[MAXV];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i)
+    if (i < nv) {
+      v[i] = xr[i * 64 + lane];
+      s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+    }
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i)
+    if (i < nv) {
+      v[i].x -= mean; v[i].y -= mean; v[i].z -= mean; v[i].w -= mean;
+      q += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+    }
+  const float rstd = rsqrtf(wave_sum(q) / (float)d + 1e-6f);
+  const float4 *sh, *sc;
+  bool plus_one;
+  if (gain) {
+    sc = (const float4*)gain; sh = (const float4*)beta; plus_one = false;
+  } else {
+    const size_t mo = (size_t)(row_req ? row_req[row] : 0) * mod_stride;
+    sc = (const float4*)(scale + mo); sh = (const float4*)(shift + mo); plus_one = true;
+  }
+  uint2* yr = (uint2*)(y + (size_t)row * d);
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i)
+    if (i < nv) {
+      float4 a = sc[i * 64 + lane], b = sh[i * 64 + lane];
+      if (plus_one) { a.x += 1.f; a.y += 1.f; a.z += 1.f; a.w += 1.f; }
+      uint2 w;
+      w.x = pack2(v[i].x * rstd * a.x + b.x, v[i].y * rstd * a.y + b.y);
+      w.y = pack2(v[i].z * rstd * a.z + b.z, v[i].w * rstd * a.w + b.w);
+      yr[i * 64 + lane] = w;
+    }
+}
+
+void launch_ln_modulate(hipStream_t s, const float* x, bf16_t* y, int M, int d, const float* shift,
+                        const float* scale, int mod_stride, const int* row_req, const float* gain,
+                        const float* beta) {
+  if (M == 0) return;
+  dim3 g((M + 3) / 4), b(256);
+  if (d <= 1024) hipLaunchKernelGGL(ln_modulate_kernel<4>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta);
+  else if (d <= 3072) hipLaunchKernelGGL(ln_modulate_kernel<12>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta);
+  else hipLaunchKernelGGL(ln_modulate_kernel<20>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta);
+}
+
+// ---------------------------------------------------------------------------------------
+// q/k per-head RMS norm (+ rotary code).  A thread owns one adjacent pair (2j, 2j+1) of one
+// head of one row; the dh/2 threads of a head reduce with shuffles.
+// ---------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void qknorm_rope_kernel(const bf16_t* __restrict__ qkv, int ld, int M, int d,
+                                                          const float* __restrict__ qgain,
+                                                          const float* __restrict__ kgain,
+                                                          const float2* __restrict__ rope,
+                                                          const int* __restrict__ dst_row,
+                                                          bf16_t* __restrict__ qo, bf16_t* __restrict__ ko,
+                                                          int ldo, int k_col_off, int do_k) {
+  const int row = blockIdx.x;
+  const int pair = blockIdx.y * 256 + threadIdx.x;     // pair index within the row's d/2 pairs
+  const bool ok = pair < (d >> 1);
+  const int col = ok ? pair * 2 : 0;
+  const int j = (col % DH) >> 1;                        // pair index within the head
+  const int drow = dst_row ? dst_row[row] : row;
+  float2 cs = make_float2(1.f, 0.f);
+  if (rope) cs = rope[(size_t)drow * (DH / 2) + j];
+#pragma unroll
+  for (int which = 0; which < 2; ++which) {
+    if (which == 1 && !do_k) break;
+    const bf16_t* src = qkv + (size_t)row * ld + (which ? k_col_off : 0) + col;
+    const uint32_t raw = *(const uint32_t*)src;
+    float x0 = bf2f((uint16_t)(raw & 0xFFFF)), x1 = bf2f((uint16_t)(raw >> 16));
+    float ss = x0 * x0 + x1 * x1;
+#pragma unroll
+    for (int o = DH / 4; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    const float r = rsqrtf(ss / (float)DH + 1e-6f);
+    const float* g = which ? kgain : qgain;
+    x0 = x0 * r * g[2 * j];
+    x1 = x1 * r * g[2 * j + 1];
+    const float y0 = x0 * cs.x - x1 * cs.y, y1 = x0 * cs.y + x1 * cs.x;
+    if (ok) *(uint32_t*)((which ? ko : qo) + (size_t)drow * ldo + col) = pack2(y0, y1);
+  }
+}
+
+void launch_qknorm_rope(hipStream_t s, const bf16_t* qkv, int ld, int M, int H, int dh, const float* qgain,
+                        const float* kgain, const float2* rope, const int* dst_row, bf16_t* qo, bf16_t* ko,
+                        int ldo, int k_col_off, int do_k) {
+  if (M == 0) return;
+  const int d = H * dh;
+  dim3 g(M, (d / 2 + 255) / 256), b(256);
+  if (dh == 64) hipLaunchKernelGGL(qknorm_rope_kernel<64>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k);
+  else hipLaunchKernelGGL(qknorm_rope_kernel<128>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k);
+}
+
+// ---------------------------------------------------------------------------------------
+// V transpose: vt[h][c][col] = v[src_of_col[col]][v_col_off + h*dh + c]   (0 where src < 0)
+// one workgroup per (64-column tile, head), through a padded LDS tile.
+// ---------------------------------------------------------------------------------------
+template <int DH>
+__global__ __launch_bounds__(256) void v_transpose_kernel(const bf16_t* __restrict__ v, int ld, int v_col_off,
+                                                          const int* __restrict__ src_of_col,
+                                                          bf16_t* __restrict__ vt, int ldvt) {
+  __shared__ uint16_t tile[64][DH + 2];
+  const int c0 = blockIdx.x * 64, h = blockIdx.y;
+  const int tid = threadIdx.x;
+  // load: 64 keys x DH values; a group of DH/2 threads reads one key row as 4-byte words
+  constexpr int TPR = DH / 2;                 // threads per key row
+  constexpr int RPP = 256 / TPR;              // key rows per pass
+#pragma unroll
+  for (int p = 0; p < 64 / RPP; ++p) {
+    const int key = p * RPP + tid / TPR, w = tid % TPR;
+    const int src = src_of_col[c0 + key];
+    uint32_t raw = 0;
+    if (src >= 0) raw = *(const uint32_t*)(v + (size_t)src * ld + v_col_off + h * DH + 2 * w);
+    tile[key][2 * w] = (uint16_t)(raw & 0xFFFF);
+    tile[key][2 * w + 1] = (uint16_t)(raw >> 16);
+  }
+  __syncthreads();
+  // store: DH rows of 64 keys; 32 threads write one row as 4-byte words
+#pragma unroll
+  for (int p = 0; p < DH / 8; ++p) {
+    const int c = p * 8 + tid / 32, w = tid % 32;
+    const uint32_t out = (uint32_t)tile[2 * w][c] | ((uint32_t)tile[2 * w + 1][c] << 16);
+    *(uint32_t*)(vt + ((size_t)h * DH + c) * ldvt + c0 + 2 * w) = out;
+  }
+}
+
+void launch_v_transpose(hipStream_t s, const bf16_t* v, int ld, int v_col_off, int H, int dh,
+                        const int* src_of_col, int n_cols_pad, bf16_t* vt, int ldvt) {
+  if (n_cols_pad == 0) return;
+  dim3 g(n_cols_pad / 64, H), b(256);
+  if (dh == 64) hipLaunchKernelGGL(v_transpose_kernel<64>, g, b, 0, s, v, ld, v_col_off, src_of_col, vt, ldvt);
+  else hipLaunchKernelGGL(v_transpose_kernel<128>, g, b, 0, s, v, ld, v_col_off, src_of_col, vt, ldvt);
+}
+
+// ---------------------------------------------------------------------------------------
+// latent update  x <- a x + b v   (one span, scalar coefficients)
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void latent_update_kernel(float* __restrict__ x, const float* __restrict__ v,
+                                                            long long n, float a, float b) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) x[i] = a * x[i] + b * v[i];
+}
+
+void launch_latent_update(hipStream_t s, float* x, const float* v, long long n, float a, float b) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(latent_update_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, v, n, a, b);
+}
+
+// ---------------------------------------------------------------------------------------
+// small-M product  y[m][n] = sum_k f(x[m][k]) W[n][k] + bias[n]   (fp32 x, bf16 W, fp32 y)
+// one wave per output column n, 8 rows of x at a time; W is read once per 8 rows.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
+
+__global__ __launch_bounds__(256) void skinny_kernel(const float* __restrict__ x, int ldx,
+                                                     const bf16_t* __restrict__ W, int ldw,
+                                                     const float* __restrict__ bias, float* __restrict__ y, int ldy,
+                                                     int M, int N, int K, int silu_in) {
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (n >= N) return;
+  const int lane = threadIdx.x & 63;
+  const bf16_t* wr = W + (size_t)n * ldw;
+  for (int m0 = 0; m0 < M; m0 += 8) {
+    float acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+    for (int k = lane * 4; k < K; k += 256) {
+      const uint2 wraw = *(const uint2*)(wr + k);
+      const float w0 = bf2f((uint16_t)(wraw.x & 0xFFFF)), w1 = bf2f((uint16_t)(wraw.x >> 16));
+      const float w2 = bf2f((uint16_t)(wraw.y & 0xFFFF)), w3 = bf2f((uint16_t)(wraw.y >> 16));
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        if (m0 + i < M) {
+          float4 xv = *(const float4*)(x + (size_t)(m0 + i) * ldx + k);
+          if (silu_in) { xv.x = silu_f(xv.x); xv.y = silu_f(xv.y); xv.z = silu_f(xv.z); xv.w = silu_f(xv.w); }
+          acc[i] += (xv.x * w0 + xv.y * w1) + (xv.z * w2 + xv.w * w3);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float t = wave_sum(acc[i]);
+      if (lane == 0 && m0 + i < M) y[(size_t)(m0 + i) * ldy + n] = t + (bias ? bias[n] : 0.f);
+    }
+  }
+}
+
+void launch_skinny(hipStream_t s, const float* x, int ldx, const bf16_t* W, int ldw, const float* bias, float* y,
+                   int ldy, int M, int N, int K, int silu_in) {
+  if (M == 0 || N == 0) return;
+  hipLaunchKernelGGL(skinny_kernel, dim3((N + 3) / 4), dim3(256), 0, s, x, ldx, W, ldw, bias, y, ldy, M, N, K, silu_in);
+}
+
+// out[m][0..127] = cos(1000 sigma f_k), out[m][128..255] = sin(...), f_k = exp(-ln(1e4) k/128)
+__global__ void timestep_features_kernel(const float* __restrict__ sigma, float* __restrict__ out, int M) {
+  const int m = blockIdx.x, k = threadIdx.x;   // 128 threads
+  if (m >= M) return;
+  const float f = expf(-9.210340371976184f * (float)k / 128.f);
+  const float ang = 1000.f * sigma[m] * f;
+  out[(size_t)m * 256 + k] = cosf(ang);
+  out[(size_t)m * 256 + 128 + k] = sinf(ang);
+}
+void launch_timestep_features(hipStream_t s, const float* sigma_dev, float* out, int M) {
+  if (M == 0) return;
+  hipLaunchKernelGGL(timestep_features_kernel, dim3(M), dim3(128), 0, s, sigma_dev, out, M);
+}
+
+// ---------------------------------------------------------------------------------------
+// patchify: token t of request r, feature ((c*pt+dt)*ph+dh)*pw+dw  <-  latent[c][f][y][x]
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void patchify_kernel(const float* __restrict__ lat,
+                                                       const long long* __restrict__ lat_off,
+                                                       const int4* __restrict__ req_dims,
+                                                       const TokInfo* __restrict__ tok, int n_img, int C,
+                                                       int pt, int ph, int pw, bf16_t* __restrict__ out, int ldp) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)n_img * ldp) return;
+  const int t = (int)(idx / ldp), feat = (int)(idx % ldp);
+  const int pdim = C * pt * ph * pw;
+  float v = 0.f;
+  if (feat < pdim) {
+    const TokInfo ti = tok[t];
+    const int4 dm = req_dims[ti.req];          // (F, H, W, -)
+    int dw = feat % pw, r = feat / pw;
+    int dh = r % ph; r /= ph;
+    int dt = r % pt; const int c = r / pt;
+    const int f = ti.f * pt + dt, yy = ti.i * ph + dh, xx = ti.j * pw + dw;
+    v = lat[lat_off[ti.req] + (((long long)c * dm.x + f) * dm.y + yy) * dm.z + xx];
+  }
+  out[idx] = f2bf(v);
+}
+void launch_patchify(hipStream_t s, const float* lat, const long long* lat_off_dev, const int4* req_dims_dev,
+                     const TokInfo* tok, int n_img, int C, int pt, int ph, int pw, bf16_t* out, int ldp) {
+  const long long total = (long long)n_img * ldp;
+  if (total == 0) return;
+  hipLaunchKernelGGL(patchify_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, lat, lat_off_dev,
+                     req_dims_dev, tok, n_img, C, pt, ph, pw, out, ldp);
+}
+
+// x[t][c] += PE(i, j)[c]:  quarters [sin(i w), cos(i w), sin(j w), cos(j w)], w_k = 1e4^(-k/(d/4))
+__global__ __launch_bounds__(256) void add_pe_kernel(float* __restrict__ x, const TokInfo* __restrict__ tok,
+                                                     int n_img, int d) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)n_img * d) return;
+  const int t = (int)(idx / d), c = (int)(idx % d);
+  const int qd = d >> 2, part = c / qd, k = c % qd;
+  const TokInfo ti = tok[t];
+  const float w = exp2f(-13.287712379549449f * (float)k / (float)qd);   // log2(1e4)
+  const float ang = (float)(part < 2 ? ti.i : ti.j) * w;
+  x[idx] += (part & 1) ? cosf(ang) : sinf(ang);
+}
+void launch_add_pe(hipStream_t s, float* x, const TokInfo* tok, int n_img, int d) {
+  const long long total = (long long)n_img * d;
+  if (total == 0) return;
+  hipLaunchKernelGGL(add_pe_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, x, tok, n_img, d);
+}
+
+// ---------------------------------------------------------------------------------------
+// unpatchify + latent update: every latent element looks up its token/feature in y
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void unpatchify_update_kernel(float* __restrict__ lat, float* __restrict__ v_out,
+                                                                const float* __restrict__ y, int ldy,
+                                                                const long long* __restrict__ lat_off,
+                                                                const int4* __restrict__ req_dims,
+                                                                const int* __restrict__ img_off,
+                                                                const float* __restrict__ a, const float* __restrict__ b,
+                                                                int n_req, long long total, int C, int pt, int ph, int pw) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= total) return;
+  int r = 0;
+  while (r + 1 < n_req && idx >= lat_off[r + 1]) ++r;
+  const int4 dm = req_dims[r];
+  long long e = idx - lat_off[r];
+  const int xx = (int)(e % dm.z); e /= dm.z;
+  const int yy = (int)(e % dm.y); e /= dm.y;
+  const int f = (int)(e % dm.x); const int c = (int)(e / dm.x);
+  const int gh = dm.y / ph, gw = dm.z / pw;
+  const int tokl = ((f / pt) * gh + yy / ph) * gw + xx / pw;
+  const int feat = ((c * pt + f % pt) * ph + yy % ph) * pw + xx % pw;
+  const float v = y[(size_t)(img_off[r] + tokl) * ldy + feat];
+  if (v_out) v_out[idx] = v;
+  lat[idx] = a[r] * lat[idx] + b[r] * v;
+}
+void launch_unpatchify_update(hipStream_t s, float* lat, float* v_out, const float* y, int ldy,
+                              const long long* lat_off_dev, const int4* req_dims_dev, const int* img_off_dev,
+                              const float* a_dev, const float* b_dev, int n_req, long long total, int C, int pt,
+                              int ph, int pw) {
+  if (total == 0) return;
+  hipLaunchKernelGGL(unpatchify_update_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, lat, v_out, y,
+                     ldy, lat_off_dev, req_dims_dev, img_off_dev, a_dev, b_dev, n_req, total, C, pt, ph, pw);
+}
+
+// ---------------------------------------------------------------------------------------
+// rotary table: out[row][j] = (cos, sin)(pos_axis * theta^(-2 jj / D_axis)); rows that are
+// not image tokens (tok_of_row < 0) get the identity rotation.
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void rope_table_kernel(const TokInfo* __restrict__ tok,
+                                                         const int* __restrict__ tok_of_row, int n_rows, int dh,
+                                                         int ax0, int ax1, int ax2, float log2_theta,
+                                                         float2* __restrict__ out) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int hp = dh >> 1;
+  if (idx >= (long long)n_rows * hp) return;
+  const int row = (int)(idx / hp), j = (int)(idx % hp);
+  const int t = tok_of_row ? tok_of_row[row] : row;
+  float2 cs = make_float2(1.f, 0.f);
+  if (t >= 0) {
+    const TokInfo ti = tok[t];
+    int e = 2 * j, width, pos;
+    if (e < ax0) { width = ax0; pos = ti.f; }
+    else if (e < ax0 + ax1) { e -= ax0; width = ax1; pos = ti.i; }
+    else { e -= ax0 + ax1; width = ax2; pos = ti.j; }
+    const float freq = exp2f(-log2_theta * (float)e / (float)width);
+    const float ang = (float)pos * freq;
+    cs = make_float2(cosf(ang), sinf(ang));
+  }
+  out[idx] = cs;
+}
+void launch_rope_table(hipStream_t s, const TokInfo* tok, const int* tok_of_row, int n_rows, int dh, int ax0,
+                       int ax1, int ax2, float theta, float2* out) {
+  const long long total = (long long)n_rows * (dh / 2);
+  if (total == 0) return;
+  hipLaunchKernelGGL(rope_table_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, tok, tok_of_row,
+                     n_rows, dh, ax0, ax1, ax2, log2f(theta), out);
+}
+
+// out[m][n] = base[m][n] + table[n]
+__global__ __launch_bounds__(256) void add_rows_kernel(const float* __restrict__ base, int ld_base,
+                                                       const float* __restrict__ table, float* __restrict__ out,
+                                                       int ld_out, int M, int N) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)M * N) return;
+  const int m = (int)(idx / N), n = (int)(idx % N);
+  out[(size_t)m * ld_out + n] = base[(size_t)m * ld_base + n] + table[n];
+}
+void launch_add_rows(hipStream_t s, const float* base, int ld_base, const float* table, float* out, int ld_out,
+                     int M, int N) {
+  const long long total = (long long)M * N;
+  if (total == 0) return;
+  hipLaunchKernelGGL(add_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, base, ld_base, table,
+                     out, ld_out, M, N);
+}
+
+// dst[dst_row[m]][:] = src[src_row[m]][:]   (float4 granules, d % 4 == 0)
+__global__ __launch_bounds__(256) void copy_rows_kernel(const float4* __restrict__ src, const int* __restrict__ src_row,
+                                                        float4* __restrict__ dst, const int* __restrict__ dst_row,
+                                                        int M, int d4) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)M * d4) return;
+  const int m = (int)(idx / d4), c = (int)(idx % d4);
+  const int sr = src_row ? src_row[m] : m, dr = dst_row ? dst_row[m] : m;
+  dst[(size_t)dr * d4 + c] = src[(size_t)sr * d4 + c];
+}
+void launch_copy_rows_f32(hipStream_t s, const float* src, const int* src_row, float* dst, const int* dst_row,
+                          int M, int d) {
+  const long long total = (long long)M * (d / 4);
+  if (total == 0) return;
+  hipLaunchKernelGGL(copy_rows_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, (const float4*)src,
+                     src_row, (float4*)dst, dst_row, M, d / 4);
+}
+
+// ---------------------------------------------------------------------------------------
+// weight initialisation: counter-based Gaussian, float64 Box-Muller (so that an independent
+// float64 host implementation of the same recipe produces bit-identical bf16 values)
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+  uint64_t z = x + 0x9E3779B97F4A7C15ull;
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+__device__ __forceinline__ float gauss(uint64_t key, uint64_t i, double std) {
+  const uint64_t z = mix64(key + i);
+  const double u1 = ((double)(z >> 40) + 1.0) * (1.0 / 16777216.0);
+  const double u2 = (double)((z >> 16) & 0xFFFFFFull) * (1.0 / 16777216.0);
+  const double g = sqrt(-2.0 * log(u1)) * cos(6.283185307179586 * u2);
+  return (float)(std * g);
+}
+// stored [rows_out][ldw]; logical element (in i, out o) has index i*rows_out + o
+__global__ __launch_bounds__(256) void init_matrix_kernel(bf16_t* __restrict__ w, int rows_out, int cols_in, int ldw,
+                                                          uint64_t key, float std) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= (long long)rows_out * cols_in) return;
+  const int o = (int)(idx / cols_in), i = (int)(idx % cols_in);
+  w[(size_t)o * ldw + i] = f2bf(gauss(key, (uint64_t)i * rows_out + o, (double)std));
+}
+void launch_init_matrix(hipStream_t s, bf16_t* w, int rows_out, int cols_in, int ldw, uint64_t key, float std) {
+  const long long total = (long long)rows_out * cols_in;
+  if (total == 0) return;
+  hipLaunchKernelGGL(init_matrix_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, w, rows_out,
+                     cols_in, ldw, key, std);
+}
+__global__ __launch_bounds__(256) void init_table_kernel(float* __restrict__ w, long long n, uint64_t key, float std) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx >= n) return;
+  w[idx] = bf2f(f2bf(gauss(key, (uint64_t)idx, (double)std)));
+}
+void launch_init_table_f32(hipStream_t s, float* w, long long n, uint64_t key, float std) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(init_table_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, w, n, key, std);
+}
+__global__ __launch_bounds__(256) void fill_f32_kernel(float* p, long long n, float v) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx < n) p[idx] = v;
+}
+void launch_fill_f32(hipStream_t s, float* p, long long n, float v) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
+}
+__global__ __launch_bounds__(256) void fill_u16_kernel(uint16_t* p, long long n, uint16_t v) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (idx < n) p[idx] = v;
+}
+void launch_fill_u16(hipStream_t s, bf16_t* p, long long n, uint16_t v) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(fill_u16_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n, v);
+}
+
+}  // namespace dit

@@ -7,7 +7,7 @@ tensor without exchanging data.
     u1   = ((z >> 40) + 1) / 2^24          in (0, 1]
     u2   = ((z >> 16) & 0xFFFFFF) / 2^24   in [0, 1)
     g    = sqrt(-2 ln u1) * cos(2 pi u2)   (float64 arithmetic)
-    out  = float32(std * g), optionally rounded to bf16 (round-to-nearest-even)
+    out  = float32(float64(float32(std)) * g), optionally rounded to bf16 (nearest-even)
 
 mix(x) is the splitmix64 output function applied to x + PHI64.
 """
@@ -57,7 +57,7 @@ def gaussian(seed: int, name: str, n: int, std: float = 1.0, start: int = 0) -> 
             u1 = ((z >> np.uint64(40)).astype(np.float64) + 1.0) * (1.0 / 16777216.0)
             u2 = ((z >> np.uint64(16)) & np.uint64(0xFFFFFF)).astype(np.float64) * (1.0 / 16777216.0)
             g = np.sqrt(-2.0 * np.log(u1)) * np.cos(two_pi * u2)
-            out[lo:hi] = (float(std) * g).astype(np.float32)
+            out[lo:hi] = (float(np.float32(std)) * g).astype(np.float32)
     return out
 
 

@@ -1,0 +1,346 @@
+"""GPU parity: the HIP path, called through the C ABI, against the float64 oracle on the
+same seeded inputs.  Tolerances are the benchmark's: per step max-abs <= 2e-2 and relative
+L2 <= 1e-2 on the model output and on the updated latent; <= 5e-2 relative L2 on the final
+latent after T steps.  Single kernels are compared at bf16-rounding level."""
+import ctypes as C
+import math
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import dit_oracle as O
+from helpers import Case, bf16_to_np, max_abs, rel_l2, to_dev_bf16
+
+pytestmark = pytest.mark.gpu
+
+STEP_MAX_ABS, STEP_REL_L2, FINAL_REL_L2 = 2e-2, 1e-2, 5e-2
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    assert torch.cuda.is_available()
+    return torch
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2510_02838_amd import binding
+    return binding
+
+
+def rnd(seed, name, shape, std=1.0):
+    return synth.gaussian_bf16(seed, name, int(np.prod(shape)), std).reshape(shape)
+
+
+# ------------------------------------------------------------------------------- weights
+def test_init_weights_matches_host_generator(torch, B):
+    """Device and host implement the same counter-based generator: bit-identical bf16."""
+    arch = synth.CONFIGS["tiny"]["arch"]
+    m = B.DiT(arch)
+    m.ensure_workspace([(1, 16, 16, 16)], 1)
+    m.init_weights(1, 0.02)
+    want = synth.make_params(O.param_shapes(arch), 1, 0.02)
+    bad = tot = 0
+    for name, r, c, k in m.tensors():
+        got = m.get_tensor(name, want[name].shape)
+        bad += int((got != want[name]).sum())
+        tot += got.size
+    assert bad <= tot * 1e-6, f"{bad} of {tot} elements differ"
+
+
+def test_set_get_tensor_round_trip(torch, B):
+    arch = synth.CONFIGS["tiny"]["arch"]
+    m = B.DiT(arch)
+    m.ensure_workspace([(1, 16, 16, 16)], 1)
+    m.init_weights(0, 0.0)
+    w = rnd(5, "w", (256, 768))
+    m.set_tensor("blk1.img.qkv.w", w)
+    assert np.array_equal(m.get_tensor("blk1.img.qkv.w", (256, 768)), w)
+    b = rnd(6, "b", (768,))
+    m.set_tensor("blk1.img.qkv.b", b)
+    assert np.array_equal(m.get_tensor("blk1.img.qkv.b", (768,)), b)
+    with pytest.raises(B.DitError):
+        m.set_tensor("blk1.img.qkv.b", np.zeros(5, np.float32))
+
+
+# ---------------------------------------------------------------------------------- GEMM
+@pytest.mark.parametrize("M,N,K", [(300, 384, 256), (1, 256, 64), (517, 1000, 192), (4250, 1536, 1536)])
+@pytest.mark.parametrize("variant", [0, 128128, 256256, 1256256, 2256256, 256128, 128256, 2128128])
+def test_gemm_against_float64_matmul(torch, B, M, N, K, variant):
+    if M > 1000 and variant not in (0, 256256, 1256256, 128128):
+        pytest.skip("large shape only for the production tiles")
+    A = rnd(1, "A", (M, K))
+    W = rnd(2, "W", (N, K), 0.05)
+    bias = rnd(3, "b", (N,), 0.5)
+    npad = (N + 255) // 256 * 256
+    Wp = np.zeros((npad, K), np.float32); Wp[:N] = W
+    dA, dW = to_dev_bf16(torch, A), to_dev_bf16(torch, Wp)
+    dB = torch.from_numpy(bias).cuda()
+    ref = A.astype(np.float64) @ W.astype(np.float64).T + bias
+    for kind in (0, 1, 2):
+        out = torch.full((M, N), float("nan"), dtype=torch.float32 if kind == 1 else torch.bfloat16, device="cuda")
+        if variant == 0:
+            st = B.dit_op_gemm(None, dA.data_ptr(), K, dW.data_ptr(), K, dB.data_ptr(), M, N, K, kind,
+                               out.data_ptr(), N, None, 0, None)
+        else:
+            st = B.dit_op_gemm_variant(None, dA.data_ptr(), K, dW.data_ptr(), K, dB.data_ptr(), M, N, K, kind,
+                                       out.data_ptr(), N, variant)
+        assert st == 0
+        torch.cuda.synchronize()
+        got = out.to(torch.float32).cpu().numpy()
+        want = O.gelu_tanh(ref) if kind == 2 else ref
+        tol = 1e-4 if kind == 1 else 2.0 ** -8          # fp32 out: accumulation order; bf16 out: half ulp
+        err = np.abs(got - want) / (np.abs(want) + 1.0)
+        assert np.isfinite(got).all()
+        assert err.max() <= tol, (kind, err.max())
+
+
+def test_gemm_gated_residual_epilogue(torch, B):
+    M, N, K, n_req = 333, 512, 128, 3
+    A, W = rnd(1, "A", (M, K)), rnd(2, "W", (N, K), 0.05)
+    bias, gate = rnd(3, "b", (N,), 0.5), synth.gaussian(4, "g", n_req * 700).reshape(n_req, 700)
+    x0 = synth.gaussian(5, "x", M * N).reshape(M, N)
+    row_req = (np.arange(M) * n_req // M).astype(np.int32)
+    dA, dW = to_dev_bf16(torch, A), to_dev_bf16(torch, W)
+    dx = torch.from_numpy(x0.copy()).cuda()
+    dg, db, dr = torch.from_numpy(gate).cuda(), torch.from_numpy(bias).cuda(), torch.from_numpy(row_req).cuda()
+    st = B.dit_op_gemm(None, dA.data_ptr(), K, dW.data_ptr(), K, db.data_ptr(), M, N, K, 3, dx.data_ptr(), N,
+                       dg[:, 100:].data_ptr(), 700, dr.data_ptr())
+    assert st == 0
+    torch.cuda.synchronize()
+    ref = x0 + gate[row_req][:, 100:100 + N].astype(np.float64) * (A.astype(np.float64) @ W.astype(np.float64).T + bias)
+    assert max_abs(dx.cpu().numpy(), ref) < 1e-4
+
+
+# ----------------------------------------------------------------------------- attention
+@pytest.mark.parametrize("dh,H", [(64, 3), (128, 2)])
+@pytest.mark.parametrize("lens", [[1], [64], [65, 7, 300], [410, 1178], [129, 128, 127, 1, 2]])
+def test_attention_against_oracle(torch, B, dh, H, lens):
+    d = H * dh
+    cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    n = int(cu[-1])
+    q, k, v = (rnd(s, nm, (n, d)) for s, nm in ((1, "q"), (2, "k"), (3, "v")))
+    q *= 2.0   # sharper softmax
+    q = synth.round_bf16(q)
+    vt_off = np.zeros(len(lens), np.int32)
+    col = 0
+    for s, L in enumerate(lens):
+        vt_off[s] = col
+        col += (L + 63) // 64 * 64
+    vt = np.zeros((H, dh, col), np.float32)
+    for s, L in enumerate(lens):
+        seg = v[cu[s]:cu[s + 1]].reshape(L, H, dh)
+        vt[:, :, vt_off[s]:vt_off[s] + L] = seg.transpose(1, 2, 0)
+    dq, dk, dvt = to_dev_bf16(torch, q), to_dev_bf16(torch, k), to_dev_bf16(torch, vt)
+    o = torch.full((n, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int))
+    wb = B.dit_op_attention_work_bytes(len(lens), ip(cu))
+    work = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    st = B.dit_op_attention(None, dq.data_ptr(), d, dk.data_ptr(), d, dvt.data_ptr(), col, o.data_ptr(), d, H, dh,
+                            len(lens), ip(cu), ip(cu), ip(vt_off), work.data_ptr(), wb)
+    assert st == 0
+    torch.cuda.synchronize()
+    got = bf16_to_np(o)
+    assert np.isfinite(got).all()
+    for s, L in enumerate(lens):
+        sl = slice(cu[s], cu[s + 1])
+        ref = O.multi_head_attention(q[sl].astype(np.float64), k[sl].astype(np.float64), v[sl].astype(np.float64), H)
+        assert max_abs(got[sl], ref) < 2e-2 and rel_l2(got[sl], ref) < 1e-2, (s, L)
+
+
+def test_attention_identical_keys_returns_mean_of_v(torch, B):
+    """Invariant checked on the GPU path itself: all keys equal => output is the mean of V."""
+    H, dh, n = 2, 64, 200
+    d = H * dh
+    q = rnd(1, "q", (n, d))
+    k = np.tile(rnd(2, "k", (1, d)), (n, 1))
+    v = rnd(3, "v", (n, d))
+    col = (n + 63) // 64 * 64
+    vt = np.zeros((H, dh, col), np.float32)
+    vt[:, :, :n] = v.reshape(n, H, dh).transpose(1, 2, 0)
+    cu, off = np.array([0, n], np.int32), np.array([0], np.int32)
+    dq, dk, dvt = to_dev_bf16(torch, q), to_dev_bf16(torch, k), to_dev_bf16(torch, vt)
+    o = torch.zeros((n, d), dtype=torch.bfloat16, device="cuda")
+    ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int))
+    wb = B.dit_op_attention_work_bytes(1, ip(cu))
+    work = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    assert B.dit_op_attention(None, dq.data_ptr(), d, dk.data_ptr(), d, dvt.data_ptr(), col, o.data_ptr(), d, H, dh,
+                              1, ip(cu), ip(cu), ip(off), work.data_ptr(), wb) == 0
+    torch.cuda.synchronize()
+    assert max_abs(bf16_to_np(o), np.tile(v.astype(np.float64).mean(0), (n, 1))) < 1e-2
+
+
+# ---------------------------------------------------------------------- row-wise kernels
+@pytest.mark.parametrize("M,d", [(1, 256), (77, 1536), (130, 3072), (9, 5120)])
+def test_ln_modulate_against_oracle(torch, B, M, d):
+    n_req = 3
+    x = (synth.gaussian(1, "x", M * d).reshape(M, d) * 3 + 1.5).astype(np.float32)
+    mod = synth.gaussian(2, "m", n_req * 2 * d, 0.3).reshape(n_req, 2 * d)
+    row_req = (np.arange(M) % n_req).astype(np.int32)
+    dx, dm, dr = torch.from_numpy(x).cuda(), torch.from_numpy(mod).cuda(), torch.from_numpy(row_req).cuda()
+    y = torch.zeros((M, d), dtype=torch.bfloat16, device="cuda")
+    assert B.dit_op_ln_modulate(None, dx.data_ptr(), y.data_ptr(), M, d, dm.data_ptr(), dm[:, d:].data_ptr(), 2 * d,
+                                dr.data_ptr()) == 0
+    torch.cuda.synchronize()
+    ref = np.stack([O.modulate(x[i].astype(np.float64), mod[row_req[i], :d], mod[row_req[i], d:]) for i in range(M)])
+    err = np.abs(bf16_to_np(y) - ref) / (np.abs(ref) + 1.0)
+    assert err.max() <= 2.0 ** -8
+
+
+def test_latent_update_op(torch, B):
+    n = 100003
+    x, v = synth.gaussian(1, "x", n), synth.gaussian(2, "v", n)
+    dx, dv = torch.from_numpy(x.copy()).cuda(), torch.from_numpy(v).cuda()
+    a, b = O.update_coefficients(1, 0.8, 0.5)
+    assert B.dit_op_latent_update(None, dx.data_ptr(), dv.data_ptr(), n, a, b) == 0
+    torch.cuda.synchronize()
+    assert max_abs(dx.cpu().numpy(), a * x.astype(np.float64) + b * v) < 1e-6
+
+
+# ------------------------------------------------------------------------- whole model
+def check_step(case, j=0, kind=0, taps=None, lat=None):
+    tap_list = []
+    if taps:
+        tap_list = [(name, 1 << 24) for name in taps]
+    xg, vg, got = case.gpu_step(j, lat, kind, tap_list)
+    xo, vo, otaps = case.oracle_step(j, lat, kind, want_taps=bool(taps))
+    for r in range(len(case.reqs)):
+        assert np.isfinite(vg[r]).all()
+        assert max_abs(vg[r], vo[r]) <= STEP_MAX_ABS, ("v", r, max_abs(vg[r], vo[r]))
+        assert rel_l2(vg[r], vo[r]) <= STEP_REL_L2, ("v", r, rel_l2(vg[r], vo[r]))
+        assert max_abs(xg[r], xo[r]) <= STEP_MAX_ABS
+        assert rel_l2(xg[r], xo[r]) <= STEP_REL_L2
+    return got, otaps
+
+
+TINY_TAPS = ["x_txt0", "x_img0", "blk0.txt.ln1", "blk0.img.ln1", "blk0.img.qkv", "blk0.q", "blk0.k", "blk0.attn",
+             "blk0.img.x_attn", "blk0.txt.x_attn", "blk0.img.mlp_act", "blk0.img.x_out", "blk1.attn",
+             "blk1.img.x_out", "final"]
+
+
+@pytest.mark.parametrize("strong", [False, True])
+def test_tiny_config_step_with_intermediates(torch, strong):
+    """Benchmark config 1 (2 joint blocks, hidden 256, 64 image + 16 text tokens).  `strong`
+    uses larger weights, random biases and gains so that attention and gates matter."""
+    cfg = synth.CONFIGS["tiny"]
+    kw = dict(std=0.06, bias_std=0.1, gain_std=0.2) if strong else {}
+    case = Case(torch, cfg["arch"], synth.make_requests("tiny"), cfg["steps"], **kw)
+    got, otaps = check_step(case, 0, 0, TINY_TAPS)
+    t = otaps[0]
+    nt = 16
+    ref = {
+        "x_txt0": t["x_txt0"], "x_img0": t["x_img0"],
+        "blk0.txt.ln1": t["blk0.txt.ln1"], "blk0.img.ln1": t["blk0.img.ln1"], "blk0.img.qkv": t["blk0.img.qkv"],
+        "blk0.q": t["blk0.q"], "blk0.k": t["blk0.k"], "blk0.attn": t["blk0.attn"],
+        "blk0.img.x_attn": t["blk0.img.x_attn"], "blk0.txt.x_attn": t["blk0.txt.x_attn"],
+        "blk0.img.mlp_act": t["blk0.img.mlp_act"], "blk0.img.x_out": t["blk0.img.x_out"],
+        "blk1.attn": t["blk1.attn"], "blk1.img.x_out": t["blk1.img.x_out"], "final": t["final"],
+    }
+    for name in TINY_TAPS:
+        g, w = got[name], ref[name]
+        assert g.shape == w.shape, (name, g.shape, w.shape)
+        assert max_abs(g, w) <= STEP_MAX_ABS * max(1.0, np.abs(w).max()), (name, max_abs(g, w))
+        assert rel_l2(g, w) <= STEP_REL_L2, (name, rel_l2(g, w))
+    assert nt == case.reqs[0][3]
+
+
+def test_tiny_config_sample_and_step_composition(torch):
+    cfg = synth.CONFIGS["tiny"]
+    case = Case(torch, cfg["arch"], synth.make_requests("tiny"), cfg["steps"], std=0.06, bias_std=0.1)
+    final_gpu = case.gpu_sample()
+    final_ora = case.oracle_sample()
+    assert rel_l2(final_gpu[0], final_ora[0]) <= FINAL_REL_L2
+    # T calls of the step equal one sample call bit for bit (same kernels, same order)
+    x = case.dev_latents()
+    for j in range(cfg["steps"]):
+        case.m.denoise_step(case.reqs, x, case.d_cond, case.sigmas[:, j], case.sigmas[:, j + 1])
+    torch.cuda.synchronize()
+    assert np.array_equal(x.cpu().numpy().reshape(final_gpu[0].shape), final_gpu[0])
+    # run-to-run determinism
+    assert np.array_equal(case.gpu_sample()[0], final_gpu[0])
+
+
+def test_tiny_golden_file(torch):
+    """The stored oracle samples (tests/golden/tiny_oracle.txt) against the GPU path."""
+    import os
+    tab = np.loadtxt(os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "tiny_oracle.txt"))
+    cfg = synth.CONFIGS["tiny"]
+    case = Case(torch, cfg["arch"], synth.make_requests("tiny"), cfg["steps"], device_init=True)
+    _, v, _ = case.gpu_step(0)
+    idx = tab[:, 0].astype(int)
+    assert max_abs(v[0].ravel()[idx], tab[:, 1]) <= STEP_MAX_ABS
+    xf = case.gpu_sample()[0]
+    assert rel_l2(xf.ravel()[idx], tab[:, 2]) <= FINAL_REL_L2
+
+
+def test_ddim_update_and_zero_weight_closed_form(torch):
+    cfg = synth.CONFIGS["tiny"]
+    case = Case(torch, cfg["arch"], synth.make_requests("tiny"), cfg["steps"], std=0.06)
+    case.sigmas = case.sigmas * 0.9
+    check_step(case, 1, kind=1)
+    zero = Case(torch, cfg["arch"], synth.make_requests("tiny"), cfg["steps"], std=0.0)
+    zero.sigmas = zero.sigmas * 0.9
+    xs = zero.gpu_sample(kind=1)
+    want = zero.lat[0] * math.sqrt((1 - zero.sigmas[0][-1] ** 2) / (1 - zero.sigmas[0][0] ** 2))
+    assert max_abs(xs[0], want) < 1e-5
+    assert np.array_equal(zero.gpu_sample(kind=0)[0], zero.lat[0])      # Euler with v = 0
+
+
+def test_heterogeneous_batch_matches_per_request_oracle(torch):
+    """Packed variable-resolution batch (the shape of benchmark config 4 at small width):
+    every request must equal the oracle run on that request alone."""
+    arch = dict(synth.CONFIGS["tiny"]["arch"], n_blocks=2)
+    reqs = [(1, 8, 8, 7), (1, 32, 24, 40), (1, 16, 16, 16), (1, 2, 2, 1), (1, 48, 40, 154)]
+    case = Case(torch, arch, reqs, 3, shifts=[1.0, 3.0, 1.5, 1.0, 2.0], std=0.06, bias_std=0.1, gain_std=0.2)
+    check_step(case, 0)
+    check_step(case, 1)
+    fg, fo = case.gpu_sample(), case.oracle_sample()
+    for r in range(len(reqs)):
+        assert rel_l2(fg[r], fo[r]) <= FINAL_REL_L2
+    # a request's result does not depend on its batch mates
+    solo = Case(torch, arch, [reqs[1]], 3, shifts=[3.0], std=0.06, bias_std=0.1, gain_std=0.2)
+    solo.lat, solo.cond = [case.lat[1]], [case.cond[1]]
+    solo.d_cond = to_dev_bf16(torch, solo.cond[0].ravel())
+    _, v_solo, _ = solo.gpu_step(0)
+    _, v_batch, _ = case.gpu_step(0)
+    assert max_abs(v_solo[0], v_batch[1]) < 1e-5
+
+
+def test_family_f_small(torch):
+    arch = dict(family="F", n_blocks=2, n_single=2, hidden=256, n_heads=2, head_dim=128, mlp_hidden=512,
+                latent_ch=16, patch=(1, 2, 2), cond_dim=128, rope_axes=(16, 56, 56), rope_theta=10000.0)
+    reqs = [(1, 16, 24, 33), (1, 8, 8, 5)]
+    case = Case(torch, arch, reqs, 2, std=0.06, bias_std=0.1, gain_std=0.2)
+    got, otaps = check_step(case, 0, 0, ["dbl0.attn", "sgl0.attn", "sgl1.x_out"])
+    # single-stream taps are in joint order: request 0 rows then request 1 rows
+    ref = np.concatenate([otaps[0]["sgl1.x_out"], otaps[1]["sgl1.x_out"]])
+    assert rel_l2(got["sgl1.x_out"], ref) <= STEP_REL_L2
+    ref = np.concatenate([otaps[0]["sgl0.attn"], otaps[1]["sgl0.attn"]])
+    assert rel_l2(got["sgl0.attn"], ref) <= STEP_REL_L2
+    fg, fo = case.gpu_sample(), case.oracle_sample()
+    for r in range(len(reqs)):
+        assert rel_l2(fg[r], fo[r]) <= FINAL_REL_L2
+
+
+def test_family_w_small(torch):
+    arch = dict(family="W", n_blocks=2, n_single=0, hidden=256, n_heads=2, head_dim=128, mlp_hidden=768,
+                latent_ch=16, patch=(1, 2, 2), cond_dim=128, rope_axes=(44, 42, 42), rope_theta=10000.0)
+    reqs = [(3, 12, 20, 40), (2, 8, 8, 70)]
+    case = Case(torch, arch, reqs, 2, std=0.06, bias_std=0.1, gain_std=0.2)
+    got, otaps = check_step(case, 0, 0, ["blk0.attn", "blk0.xattn", "blk1.x_out"])
+    for name in ("blk0.attn", "blk0.xattn", "blk1.x_out"):
+        ref = np.concatenate([otaps[0][name], otaps[1][name]])
+        assert rel_l2(got[name], ref) <= STEP_REL_L2, name
+    fg, fo = case.gpu_sample(), case.oracle_sample()
+    for r in range(len(reqs)):
+        assert rel_l2(fg[r], fo[r]) <= FINAL_REL_L2
+
+
+def test_sd3_width_two_blocks_full_tokens(torch):
+    """Benchmark config 2 at full width and token count (4096 image + 154 text tokens, hidden
+    1536, 24 heads), depth cut to 2 blocks so the oracle finishes in seconds."""
+    arch = dict(synth.CONFIGS["sd3"]["arch"], n_blocks=2)
+    case = Case(torch, arch, synth.make_requests("sd3"), 2)
+    check_step(case, 0)

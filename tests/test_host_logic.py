@@ -1,0 +1,105 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, and its
+host logic (tensor table, size queries, argument validation) behaves.  No kernel runs."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+from oracle import dit_oracle as O
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2510_02838_amd import binding
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    hdr = open(os.path.join(ROOT, "include", "dit.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(dit_[a-z_0-9]+)\s*\(", hdr))
+    assert len(declared) >= 20
+    for name in declared:
+        assert hasattr(B.lib, name), f"{name} declared in dit.h but not exported"
+    assert declared == set(B.EXPORTS)
+
+
+@pytest.mark.parametrize("name", list(synth.CONFIGS))
+def test_tensor_table_matches_oracle_parameter_list(B, name):
+    arch = synth.CONFIGS[name]["arch"]
+    m = B.DiT(arch, bind=False)
+    shapes = O.param_shapes(arch)
+    table = m.tensors()
+    assert [t[0] for t in table] == list(shapes.keys())
+    kinds = {"matrix": 0, "bias": 1, "gain": 2, "table": 3}
+    for tname, r, c, k in table:
+        shape, kind = shapes[tname]
+        assert k == kinds[kind]
+        assert (r, c) == (tuple(shape) if len(shape) == 2 else (1, shape[0]))
+    # arena holds every matrix in bf16 (padded) and every vector in fp32
+    n_params = sum(int(np.prod(s)) for s, _ in shapes.values())
+    assert 2 * n_params <= m.weight_bytes() <= 2.2 * n_params + (1 << 22)
+    m.close()
+
+
+def test_workspace_size_grows_with_batch_and_steps(B):
+    arch = synth.CONFIGS["tiny"]["arch"]
+    m = B.DiT(arch, bind=False)
+    a = m.workspace_bytes([(1, 16, 16, 16)], 4)
+    b = m.workspace_bytes([(1, 16, 16, 16), (1, 32, 32, 16)], 4)
+    c = m.workspace_bytes([(1, 16, 16, 16)], 28)
+    assert 0 < a < b and a < c
+    assert m.workspace_bytes([(1, 15, 16, 16)], 4) == 0      # not divisible by the patch
+    assert m.workspace_bytes([(2, 16, 16, 16)], 4) == 0      # family J is single-frame
+    assert m.workspace_bytes([(1, 16, 16, 0)], 4) == 0       # empty condition
+    assert m.workspace_bytes([], 4) == 0
+    assert m.workspace_bytes([(1, 16, 16, 16)], 0) == 0
+    m.close()
+
+
+def test_create_rejects_bad_configurations(B):
+    base = synth.CONFIGS["tiny"]["arch"]
+    def status(**kw):
+        arch = dict(base); arch.update(kw)
+        cfg = B.make_config(arch)
+        ctx = C.c_void_p()
+        st = B.dit_create(C.byref(cfg), 0, None, C.byref(ctx))
+        if st == 0:
+            B.dit_destroy(ctx)
+        else:
+            assert not ctx.value
+        return st
+    assert status() == 0
+    assert status(hidden=250) == 2
+    assert status(n_heads=3) == 2
+    assert status(head_dim=32, n_heads=8) == 2
+    assert status(mlp_hidden=1000) == 2
+    assert status(cond_dim=100) == 2
+    assert status(rope_axes=(10, 10, 10)) == 2
+    assert status(n_single=3) == 2
+    assert status(rope_axes=(16, 24, 24)) == 5       # rotary code with family J
+    assert B.dit_create(None, 0, None, None) == 1
+
+
+def test_calls_fail_cleanly_without_buffers(B):
+    m = B.DiT(synth.CONFIGS["tiny"]["arch"], bind=False)
+    assert B.dit_init_weights(m.ctx, 1, 0.02) == 1
+    assert b"dit_bind" in B.dit_last_error(m.ctx)
+    a = np.zeros(4, np.float32)
+    assert B.dit_set_tensor(m.ctx, b"nope", a.ctypes.data_as(C.POINTER(C.c_float)), 4) == 1
+    assert B.dit_bind(m.ctx, None, 0, None, 0) == 1
+    assert B.dit_bind(m.ctx, 256, 16, 512, 16) == 3          # arena too small (never dereferenced)
+    assert B.dit_bind(m.ctx, 257, 1 << 30, 512, 16) == 1     # misaligned
+    reqs = B.make_reqs([(1, 16, 16, 16)])
+    s = np.zeros(1, np.float32).ctypes.data_as(C.POINTER(C.c_float))
+    assert B.dit_denoise_step(m.ctx, 1, reqs, 256, 256, s, s, 0, None) == 1   # nothing bound
+    assert B.dit_denoise_step(None, 1, reqs, 256, 256, s, s, 0, None) == 1
+    assert B.dit_op_gemm(None, None, 0, None, 0, None, 1, 1, 64, 0, None, 1, None, 0, None) == 1
+    assert B.dit_op_gemm(None, 256, 64, 256, 64, None, 4, 4, 65, 0, 256, 4, None, 0, None) == 2
+    assert B.dit_op_attention_work_bytes(0, None) == 0
+    m.close()
