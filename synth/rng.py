@@ -11,6 +11,8 @@ tensor without exchanging data.
 
 mix(x) is the splitmix64 output function applied to x + PHI64.
 """
+import os
+
 import numpy as np
 
 PHI64 = 0x9E3779B97F4A7C15
@@ -43,21 +45,29 @@ def tensor_key(seed: int, name: str) -> int:
     return _mix_int((seed & _M64) ^ ((fnv1a64(name) * PHI64) & _M64))
 
 
+def _gaussian_chunk(key, out, lo, hi, start, std):
+    with np.errstate(over="ignore"):
+        idx = np.arange(start + lo, start + hi, dtype=np.uint64)
+        z = _mix_vec(key + idx)
+        u1 = ((z >> np.uint64(40)).astype(np.float64) + 1.0) * (1.0 / 16777216.0)
+        u2 = ((z >> np.uint64(16)) & np.uint64(0xFFFFFF)).astype(np.float64) * (1.0 / 16777216.0)
+        g = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+        out[lo:hi] = (float(np.float32(std)) * g).astype(np.float32)
+
+
 def gaussian(seed: int, name: str, n: int, std: float = 1.0, start: int = 0) -> np.ndarray:
     """float32 array of n values, elements start..start+n-1 of tensor `name`."""
     key = np.uint64(tensor_key(seed, name))
     out = np.empty(n, dtype=np.float32)
-    chunk = 1 << 22
-    two_pi = 2.0 * np.pi
-    with np.errstate(over="ignore"):
-        for lo in range(0, n, chunk):
-            hi = min(n, lo + chunk)
-            idx = np.arange(start + lo, start + hi, dtype=np.uint64)
-            z = _mix_vec(key + idx)
-            u1 = ((z >> np.uint64(40)).astype(np.float64) + 1.0) * (1.0 / 16777216.0)
-            u2 = ((z >> np.uint64(16)) & np.uint64(0xFFFFFF)).astype(np.float64) * (1.0 / 16777216.0)
-            g = np.sqrt(-2.0 * np.log(u1)) * np.cos(two_pi * u2)
-            out[lo:hi] = (float(np.float32(std)) * g).astype(np.float32)
+    chunk = 1 << 20
+    spans = [(lo, min(n, lo + chunk)) for lo in range(0, n, chunk)]
+    if len(spans) <= 2:
+        for lo, hi in spans:
+            _gaussian_chunk(key, out, lo, hi, start, std)
+    else:   # NumPy releases the GIL inside its loops, so threads scale
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(8, os.cpu_count() or 1)) as ex:
+            list(ex.map(lambda s: _gaussian_chunk(key, out, s[0], s[1], start, std), spans))
     return out
 
 
