@@ -5,14 +5,21 @@
 //
 // Tiling.  A workgroup owns a BM x BN tile of C and walks K in slabs of 64.  Slabs of A and
 // W go from global memory straight into LDS (global_load_lds_dwordx4: each lane deposits 16
-// bytes at wave-base + 16*lane, no staging registers), double buffered with one barrier per
-// slab.  Which 16-byte chunk a lane fetches is XOR-swizzled on the global side, so that the
-// 128-bit LDS reads that feed the MFMA operands are bank-conflict free.  (DIRECT = false
-// keeps a register-staged copy path, for comparison.)  A wave owns a (BM/WM) x (BN/WN) sub-tile made of 32x32 MFMA tiles
-// (v_mfma_f32_32x32x16_bf16: 64 lanes, A operand = 32 rows x 16 k, B operand = 16 k x 32
-// columns, each lane supplies 8 consecutive k).  MFMA rows are rows of A (tokens), MFMA
-// columns are rows of W (output features), so the 32 lanes of a half-wave write 32
-// consecutive output features of one token.
+// bytes at wave-base + 16*lane, no staging registers) into a two-stage ring.  Which 16-byte
+// chunk a lane fetches is XOR-swizzled on the global side, so that the 128-bit LDS reads
+// that feed the MFMA operands are bank-conflict free (LDS on gfx950 serves 16 lanes x 16
+// bytes per clock from 64 banks: 16 consecutive rows of 128 bytes need 16 distinct
+// (row parity, chunk) pairs, hence the key (row >> 1) & 7).  A wave owns a (BM/WM) x (BN/WN)
+// sub-tile made of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16: 64 lanes, A operand = 32 rows
+// x 16 k, B operand = 16 k x 32 columns, each lane supplies 8 consecutive k).  MFMA rows are
+// rows of A (tokens), MFMA columns are rows of W (output features), so the 32 lanes of a
+// half-wave write 32 consecutive output features of one token.
+//
+// Pipeline.  Operand fragments are double buffered in registers: while the MFMAs of k-step
+// kk run, the fragments of kk+1 are read from LDS.  The one barrier per slab sits between
+// k-steps 2 and 3: by then every wave holds the slab's last fragments in registers, so the
+// slab's LDS stage is free for the loads of slab+2, and the next slab (landed one slab-time
+// ago) becomes visible, so k-step 3 can already prefetch the next slab's first fragments.
 //
 // Several problems (for example the text and the image stream of one joint block, which
 // have different weights) are launched as one grid.  Workgroup ids are first de-interleaved
@@ -42,13 +49,28 @@ __device__ __forceinline__ float gelu_tanh(float x) {
   return x / (1.0f + __expf(-2.0f * u));
 }
 
-// byte offset of 16-byte chunk `c` (0..7) of slab row `r`
-__device__ __forceinline__ int swz(int r, int c) { return r * ROW_BYTES + ((c ^ ((r >> 1) & 7)) << 4); }
+__device__ __forceinline__ int swz_key(int r) { return (r >> 1) & 7; }
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
-template <int BM, int BN, int WM, int WN, bool DIRECT>
+#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+// scheduling hint for one k-step: NR LDS reads spread over NM MFMAs
+template <int NR, int NM>
+__device__ __forceinline__ void interleave_hint() {
+  constexpr int per = NM / NR, extra = NM - per * NR;
+#pragma unroll
+  for (int i = 0; i < NR; ++i) {
+    SGB(0x100, 1);      // one DS read
+    SGB(0x008, per);    // `per` MFMAs
+  }
+  if (extra > 0) SGB(0x008, extra);
+}
+
+// PIPE: 1 = production loop; 0 = plain loop (fragments read right before use); 2 and 3 are
+// measurement probes (global->LDS traffic only / LDS reads + MFMAs only) whose output is
+// meaningless.
+template <int BM, int BN, int WM, int WN, int PIPE>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batch) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -79,21 +101,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     tn = r / gsz;
   }
   const int m0 = tm * BM, n0 = tn * BN;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave / WN, wn = wave % WN;
 
-  // ---- per-thread global source pointers -----------------------------------------------
+  // ---- per-thread global source offsets ------------------------------------------------
   // (element offsets from the matrix base; every operand is far below 2^31 elements)
   uint32_t ga[LA], gb[LB];
 #pragma unroll
   for (int i = 0; i < LA; ++i) {
-    int q = i * NT + tid, r = q >> 3, pc = q & 7, c = pc ^ ((r >> 1) & 7);
+    int q = i * NT + tid, r = q >> 3, pc = q & 7, c = pc ^ swz_key(r);
     int m = m0 + r; if (m >= P.M) m = P.M - 1;            // clamp: rows past M are never stored
     ga[i] = (uint32_t)m * (uint32_t)P.lda + c * 8;
   }
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
-    int q = i * NT + tid, r = q >> 3, pc = q & 7, c = pc ^ ((r >> 1) & 7);
+    int q = i * NT + tid, r = q >> 3, pc = q & 7, c = pc ^ swz_key(r);
     gb[i] = (uint32_t)(n0 + r) * (uint32_t)P.ldw + c * 8; // weights are padded to N_pad rows
   }
 
@@ -106,78 +129,122 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int nk = P.K / BK;
+  const int half = lane >> 5;
+  // LDS byte offsets of this lane's fragment rows (the chunk index is XORed in per k-step;
+  // the key is the same for rows 32 apart)
   const int arow = wm * (BM / WM) + (lane & 31);
   const int brow = wn * (BN / WN) + (lane & 31);
-  const int half = lane >> 5;
+  const int akey = swz_key(arow), bkey = swz_key(brow);
+  const int abase = arow * ROW_BYTES, bbase = OFFB + brow * ROW_BYTES;
 
-  auto compute = [&](const unsigned char* cA, const unsigned char* cB) {
+  // chunk q = i*NT + tid lands at LDS byte q*16 = (i*NT + wave*64)*16 + lane*16
+  auto issue = [&](int kt, unsigned char* dA) {
+    const bf16_t* Ak = P.A + kt * BK;
+    const bf16_t* Wk = P.W + kt * BK;
+    unsigned char* dB = dA + OFFB;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      bf16x8 a[TM], b[TN];
-      const int c = kk * 2 + half;
+    for (int i = 0; i < LA; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(Ak + ga[i]), (lptr_t)(dA + (i * NT + wave * 64) * 16), 16, 0, 0);
 #pragma unroll
-      for (int i = 0; i < TM; ++i) a[i] = *(const bf16x8*)(cA + swz(arow + i * 32, c));
+    for (int i = 0; i < LB; ++i)
+      __builtin_amdgcn_global_load_lds((gptr_t)(Wk + gb[i]), (lptr_t)(dB + (i * NT + wave * 64) * 16), 16, 0, 0);
+  };
+  auto load_frags = [&](const unsigned char* st, int kk, bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
+    const int c = kk * 2 + half;
+    const unsigned char* pa = st + abase + ((c ^ akey) << 4);
+    const unsigned char* pb = st + bbase + ((c ^ bkey) << 4);
 #pragma unroll
-      for (int j = 0; j < TN; ++j) b[j] = *(const bf16x8*)(cB + swz(brow + j * 32, c));
+    for (int i = 0; i < TM; ++i) a[i] = *(const bf16x8*)(pa + i * 32 * ROW_BYTES);
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+    for (int j = 0; j < TN; ++j) b[j] = *(const bf16x8*)(pb + j * 32 * ROW_BYTES);
+  };
+  auto mfma_all = [&](const bf16x8 (&a)[TM], const bf16x8 (&b)[TN]) {
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
 
-  if constexpr (DIRECT) {
-    // chunk q = i*NT + tid lands at LDS byte q*16 = (i*NT + wave*64)*16 + lane*16
-    auto issue = [&](int kt, unsigned char* dA) {
-      const bf16_t* Ak = P.A + kt * BK;
-      const bf16_t* Wk = P.W + kt * BK;
-      unsigned char* dB = dA + OFFB;
-#pragma unroll
-      for (int i = 0; i < LA; ++i)
-        __builtin_amdgcn_global_load_lds((gptr_t)(Ak + ga[i]), (lptr_t)(dA + (i * NT + wave * 64) * 16), 16, 0, 0);
-#pragma unroll
-      for (int i = 0; i < LB; ++i)
-        __builtin_amdgcn_global_load_lds((gptr_t)(Wk + gb[i]), (lptr_t)(dB + (i * NT + wave * 64) * 16), 16, 0, 0);
-    };
+  if constexpr (PIPE == 2) {
+    // probe: the global->LDS traffic of the real loop without MFMA work
+    issue(0, smem);
+    for (int kt = 0; kt < nk; ++kt) {
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      __syncthreads();
+      if (kt + 1 < nk) issue(kt + 1, smem + ((kt + 1) & 1) * STAGE);
+    }
+    bf16x8 a[TM], b[TN];
+    load_frags(smem, 0, a, b);
+    mfma_all(a, b);
+  } else if constexpr (PIPE == 3) {
+    // probe: LDS fragment reads + MFMAs of the real loop, global loads for slabs 0 and 1 only
+    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+    issue(0, smem);
+    issue(nk > 1 ? 1 : 0, smem + STAGE);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    load_frags(smem, 0, a0, b0);
+    for (int kt = 0; kt < nk; ++kt) {
+      const unsigned char* cur = smem + (kt & 1) * STAGE;
+      const unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+      load_frags(cur, 1, a1, b1);
+      mfma_all(a0, b0);
+      interleave_hint<TM + TN, TM * TN>();
+      load_frags(cur, 2, a0, b0);
+      mfma_all(a1, b1);
+      interleave_hint<TM + TN, TM * TN>();
+      load_frags(cur, 3, a1, b1);
+      mfma_all(a0, b0);
+      interleave_hint<TM + TN, TM * TN>();
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      __syncthreads();
+      load_frags(nxt, 0, a0, b0);
+      mfma_all(a1, b1);
+      interleave_hint<TM + TN, TM * TN>();
+    }
+  } else if constexpr (PIPE == 0) {
+    // plain loop: one barrier per slab, fragments read right before use
     issue(0, smem);
     for (int kt = 0; kt < nk; ++kt) {
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // my part of slab kt has landed
       __syncthreads();                                   // everyone's has; slab kt-1 is free
       if (kt + 1 < nk) issue(kt + 1, smem + ((kt + 1) & 1) * STAGE);
-      const unsigned char* cA = smem + (kt & 1) * STAGE;
-      compute(cA, cA + OFFB);
+      const unsigned char* cur = smem + (kt & 1) * STAGE;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 a[TM], b[TN];
+        load_frags(cur, kk, a, b);
+        mfma_all(a, b);
+      }
     }
   } else {
-    u32x4 ra[LA], rb[LB];
-#pragma unroll
-    for (int i = 0; i < LA; ++i) ra[i] = *(const u32x4*)(P.A + ga[i]);
-#pragma unroll
-    for (int i = 0; i < LB; ++i) rb[i] = *(const u32x4*)(P.W + gb[i]);
-#pragma unroll
-    for (int i = 0; i < LA; ++i) *(u32x4*)(smem + (i * NT + tid) * 16) = ra[i];
-#pragma unroll
-    for (int i = 0; i < LB; ++i) *(u32x4*)(smem + OFFB + (i * NT + tid) * 16) = rb[i];
+    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+    issue(0, smem);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
+    if (nk > 1) issue(1, smem + STAGE);
+    load_frags(smem, 0, a0, b0);
     for (int kt = 0; kt < nk; ++kt) {
-      const unsigned char* cA = smem + (kt & 1) * STAGE;
-      unsigned char* nA = smem + ((kt & 1) ^ 1) * STAGE;
-      {
-        // prefetch the next slab (the last iteration re-reads its own slab; the copy is unused)
-        const int ko = (kt + 1 < nk ? kt + 1 : kt) * BK;
-        const bf16_t* Ak = P.A + ko;
-        const bf16_t* Wk = P.W + ko;
-#pragma unroll
-        for (int i = 0; i < LA; ++i) ra[i] = *(const u32x4*)(Ak + ga[i]);
-#pragma unroll
-        for (int i = 0; i < LB; ++i) rb[i] = *(const u32x4*)(Wk + gb[i]);
-      }
-      compute(cA, cA + OFFB);
-#pragma unroll
-      for (int i = 0; i < LA; ++i) *(u32x4*)(nA + (i * NT + tid) * 16) = ra[i];
-#pragma unroll
-      for (int i = 0; i < LB; ++i) *(u32x4*)(nA + OFFB + (i * NT + tid) * 16) = rb[i];
+      const unsigned char* cur = smem + (kt & 1) * STAGE;
+      const unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+      load_frags(cur, 1, a1, b1);
+      mfma_all(a0, b0);
+      interleave_hint<TM + TN, TM * TN>();
+      load_frags(cur, 2, a0, b0);
+      mfma_all(a1, b1);
+      interleave_hint<TM + TN, TM * TN>();
+      load_frags(cur, 3, a1, b1);
+      mfma_all(a0, b0);
+      interleave_hint<TM + TN, TM * TN>();
+      // the last fragments of this slab are on their way to registers; slab kt+1 was issued
+      // one slab ago.  After the barrier nobody reads `cur` any more and `nxt` is visible.
+      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
       __syncthreads();
+      if (kt + 2 < nk) issue(kt + 2, smem + (kt & 1) * STAGE);
+      load_frags(nxt, 0, a0, b0);          // (after the last slab this reads stale LDS; unused)
+      mfma_all(a1, b1);
+      interleave_hint<TM + TN, TM * TN>();
     }
   }
 
@@ -222,7 +289,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   else epilogue(std::integral_constant<int, OUT_RESID_F32>{});
 }
 
-template <int BM, int BN, int WM, int WN, bool DIRECT>
+template <int BM, int BN, int WM, int WN, int PIPE>
 static void launch_t(hipStream_t s, GemmBatch& b) {
   int total = 0;
   for (int i = 0; i < b.n; ++i) {
@@ -235,7 +302,7 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
   b.total_tiles = total;
   if (total == 0) return;
   size_t lds = 2 * (BM + BN) * ROW_BYTES;
-  auto kern = gemm_kernel<BM, BN, WM, WN, DIRECT>;
+  auto kern = gemm_kernel<BM, BN, WM, WN, PIPE>;
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -244,7 +311,8 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
   hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), lds, s, b);
 }
 
-// variant codes: BM*1000 + BN, +1e6 for 8 waves (2x4), +2e6 for the register-staged path
+// variant codes: BM*1000 + BN; +1000000 = 8 waves (2x4) instead of 4 (2x2);
+// +2000000 = plain (non-pipelined) main loop; 6256256 / 7256256 = measurement probes
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
   // Tile choice: the big tile has the best MFMA-per-byte ratio but needs enough tiles to
   // fill 256 CUs; otherwise fall back to smaller tiles.
@@ -253,16 +321,19 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     long long t256 = 0;
     for (int i = 0; i < b.n; ++i)
       t256 += (long long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
-    tile = (t256 >= 480) ? 256256 : 128128;
+    tile = (t256 >= 480) ? 1256256 : 128128;
   }
   switch (tile) {
-    case 256256: launch_t<256, 256, 2, 2, true>(s, b); break;
-    case 1256256: launch_t<256, 256, 2, 4, true>(s, b); break;
-    case 2256256: launch_t<256, 256, 2, 2, false>(s, b); break;
-    case 256128: launch_t<256, 128, 2, 2, true>(s, b); break;
-    case 128256: launch_t<128, 256, 2, 2, true>(s, b); break;
-    case 2128128: launch_t<128, 128, 2, 2, false>(s, b); break;
-    default: tile = 128128; launch_t<128, 128, 2, 2, true>(s, b); break;
+    case 256256: launch_t<256, 256, 2, 2, 1>(s, b); break;
+    case 1256256: launch_t<256, 256, 2, 4, 1>(s, b); break;
+    case 2256256: launch_t<256, 256, 2, 2, 0>(s, b); break;
+    case 3256256: launch_t<256, 256, 2, 4, 0>(s, b); break;
+    case 6256256: launch_t<256, 256, 2, 4, 2>(s, b); break;
+    case 7256256: launch_t<256, 256, 2, 4, 3>(s, b); break;
+    case 256128: launch_t<256, 128, 2, 2, 1>(s, b); break;
+    case 128256: launch_t<128, 256, 2, 2, 1>(s, b); break;
+    case 2128128: launch_t<128, 128, 2, 2, 0>(s, b); break;
+    default: tile = 128128; launch_t<128, 128, 2, 2, 1>(s, b); break;
   }
   return tile;
 }
