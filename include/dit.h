@@ -172,7 +172,8 @@ dit_status dit_op_gemm(void* stream, const void* A, int lda, const void* W, int 
 
 /* As dit_op_gemm (out_kind 0..2 only) with the tile variant forced, for tuning sweeps:
  * BM*1000+BN in {256256, 256128, 128256, 128128}; +1000000 = 8 waves (256256 only);
- * +2000000 = plain main loop without register double-buffering (256256, 128128). */
+ * +10000000 / +20000000 = k-slab 32 with a 4- / 5-stage LDS ring instead of k-slab 64 with
+ * 2 stages (256256, 1256256, 128128). */
 dit_status dit_op_gemm_variant(void* stream, const void* A, int lda, const void* W, int ldw,
                                const float* bias, int M, int N, int K, int out_kind, void* out,
                                int ldc, int variant);

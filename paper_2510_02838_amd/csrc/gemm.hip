@@ -3,23 +3,27 @@
 // Used for every dense contraction of the denoising step except attention: QKV, attention
 // output projection, both MLP matmuls, the embeddings and the final projection.
 //
-// Tiling.  A workgroup owns a BM x BN tile of C and walks K in slabs of 64.  Slabs of A and
-// W go from global memory straight into LDS (global_load_lds_dwordx4: each lane deposits 16
-// bytes at wave-base + 16*lane, no staging registers) into a two-stage ring.  Which 16-byte
-// chunk a lane fetches is XOR-swizzled on the global side, so that the 128-bit LDS reads
-// that feed the MFMA operands are bank-conflict free (LDS on gfx950 serves 16 lanes x 16
-// bytes per clock from 64 banks: 16 consecutive rows of 128 bytes need 16 distinct
-// (row parity, chunk) pairs, hence the key (row >> 1) & 7).  A wave owns a (BM/WM) x (BN/WN)
-// sub-tile made of 32x32 MFMA tiles (v_mfma_f32_32x32x16_bf16: 64 lanes, A operand = 32 rows
-// x 16 k, B operand = 16 k x 32 columns, each lane supplies 8 consecutive k).  MFMA rows are
-// rows of A (tokens), MFMA columns are rows of W (output features), so the 32 lanes of a
-// half-wave write 32 consecutive output features of one token.
+// Tiling.  A workgroup owns a BM x BN tile of C and walks K in slabs of BK (32 or 64).  Slabs
+// of A and W go from global memory straight into LDS (global_load_lds_dwordx4: each lane
+// deposits 16 bytes at wave-base + 16*lane, no staging registers) into a ring of NS stages.
+// Which 16-byte chunk a lane fetches is XOR-swizzled on the global side, so that the 128-bit
+// LDS reads that feed the MFMA operands are bank-conflict free (LDS on gfx950 serves 16 lanes
+// x 16 bytes per clock from 64 banks: 16 consecutive slab rows must fall into 16 distinct
+// 16-byte slots of a 256-byte window; the key is (row >> 1) & 7 for 128-byte rows and
+// (row >> 2) & 3 for 64-byte rows).  A wave owns a (BM/WM) x (BN/WN) sub-tile made of 32x32
+// MFMA tiles (v_mfma_f32_32x32x16_bf16: 64 lanes, A operand = 32 rows x 16 k, B operand =
+// 16 k x 32 columns, each lane supplies 8 consecutive k).  MFMA rows are rows of A (tokens),
+// MFMA columns are rows of W (output features), so the 32 lanes of a half-wave write 32
+// consecutive output features of one token.
 //
-// Pipeline.  Operand fragments are double buffered in registers: while the MFMAs of k-step
-// kk run, the fragments of kk+1 are read from LDS.  The one barrier per slab sits between
-// k-steps 2 and 3: by then every wave holds the slab's last fragments in registers, so the
-// slab's LDS stage is free for the loads of slab+2, and the next slab (landed one slab-time
-// ago) becomes visible, so k-step 3 can already prefetch the next slab's first fragments.
+// Pipeline.  NS-1 slabs are in flight from global memory while one is computed: measured on
+// MI355X a 64 KB slab takes about 1.4 us from issue to landing, as long as its MFMA work, so
+// a single slab in flight leaves the matrix cores waiting.  Operand fragments are double
+// buffered in registers: while the MFMAs of k-step kk run, the fragments of kk+1 are read
+// from LDS.  The one barrier per slab sits before the slab's last k-step: by then every wave
+// holds the slab's last fragments in registers, so the slab's stage is free for the loads of
+// slab+NS, and the next slab becomes visible, so the last k-step already prefetches the next
+// slab's first fragments.
 //
 // Several problems (for example the text and the image stream of one joint block, which
 // have different weights) are launched as one grid.  Workgroup ids are first de-interleaved
@@ -34,8 +38,6 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-static constexpr int BK = 64;          // k-slab, elements
-static constexpr int ROW_BYTES = 128;  // one slab row in LDS
 
 __device__ __forceinline__ uint16_t f2bf(float f) {
   uint32_t u = __float_as_uint(f);
@@ -49,7 +51,8 @@ __device__ __forceinline__ float gelu_tanh(float x) {
   return x / (1.0f + __expf(-2.0f * u));
 }
 
-__device__ __forceinline__ int swz_key(int r) { return (r >> 1) & 7; }
+template <int BKT>
+__device__ __forceinline__ int swz_key(int r) { return BKT == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -66,19 +69,30 @@ __device__ __forceinline__ void interleave_hint() {
   }
   if (extra > 0) SGB(0x008, extra);
 }
+// s_waitcnt immediate for "at most N vector-memory loads outstanding" (and LDS reads done if LGKM0)
+template <int N, bool LGKM0>
+__device__ __forceinline__ void wait_vm() {
+  constexpr int imm = (N & 15) | ((N >> 4) << 14) | (7 << 4) | ((LGKM0 ? 0 : 15) << 8);
+  __builtin_amdgcn_s_waitcnt(imm);
+  asm volatile("" ::: "memory");
+}
 
-// PIPE: 1 = production loop; 0 = plain loop (fragments read right before use); 2 and 3 are
-// measurement probes (global->LDS traffic only / LDS reads + MFMAs only) whose output is
-// meaningless.
-template <int BM, int BN, int WM, int WN, int PIPE>
+// MODE: 0 = production; 2 and 3 are measurement probes (global->LDS traffic only / LDS reads
+// + MFMAs only) whose output is meaningless.
+template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batch) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
-  constexpr int LA = BM * 8 / NT, LB = BN * 8 / NT;   // 16-byte chunks per thread per slab
-  static_assert(BM * 8 % NT == 0 && BN * 8 % NT == 0, "tile/threads");
+  constexpr int ROWB = BKT * 2;                        // bytes of one slab row in LDS
+  constexpr int CPR = BKT / 8;                         // 16-byte chunks per slab row
+  constexpr int KK = BKT / 16;                         // k-steps per slab (2 or 4)
+  constexpr int LA = BM * CPR / NT, LB = BN * CPR / NT;   // chunks per thread per slab
+  constexpr int LPS = LA + LB;
+  static_assert(BM * CPR % NT == 0 && BN * CPR % NT == 0, "tile/threads");
+  static_assert((NS - 1) * LPS < 64, "vmcnt range");
   extern __shared__ __attribute__((aligned(128))) unsigned char smem[];
-  constexpr int STAGE = (BM + BN) * ROW_BYTES;   // one slab of A then one slab of W
-  constexpr int OFFB = BM * ROW_BYTES;
+  constexpr int STAGE = (BM + BN) * ROWB;   // one slab of A then one slab of W
+  constexpr int OFFB = BM * ROWB;
 
   // ---- workgroup -> (problem, tile) ----------------------------------------------------
   int bid = blockIdx.x, nb = gridDim.x;
@@ -110,13 +124,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   uint32_t ga[LA], gb[LB];
 #pragma unroll
   for (int i = 0; i < LA; ++i) {
-    int q = i * NT + tid, r = q >> 3, pc = q & 7, c = pc ^ swz_key(r);
+    int q = i * NT + tid, r = q / CPR, pc = q % CPR, c = pc ^ swz_key<BKT>(r);
     int m = m0 + r; if (m >= P.M) m = P.M - 1;            // clamp: rows past M are never stored
     ga[i] = (uint32_t)m * (uint32_t)P.lda + c * 8;
   }
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
-    int q = i * NT + tid, r = q >> 3, pc = q & 7, c = pc ^ swz_key(r);
+    int q = i * NT + tid, r = q / CPR, pc = q % CPR, c = pc ^ swz_key<BKT>(r);
     gb[i] = (uint32_t)(n0 + r) * (uint32_t)P.ldw + c * 8; // weights are padded to N_pad rows
   }
 
@@ -128,19 +142,23 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int nk = P.K / BK;
+  const int nk = P.K / BKT;
   const int half = lane >> 5;
   // LDS byte offsets of this lane's fragment rows (the chunk index is XORed in per k-step;
   // the key is the same for rows 32 apart)
   const int arow = wm * (BM / WM) + (lane & 31);
   const int brow = wn * (BN / WN) + (lane & 31);
-  const int akey = swz_key(arow), bkey = swz_key(brow);
-  const int abase = arow * ROW_BYTES, bbase = OFFB + brow * ROW_BYTES;
+  const int akey = swz_key<BKT>(arow), bkey = swz_key<BKT>(brow);
+  const int abase = arow * ROWB, bbase = OFFB + brow * ROWB;
 
-  // chunk q = i*NT + tid lands at LDS byte q*16 = (i*NT + wave*64)*16 + lane*16
-  auto issue = [&](int kt, unsigned char* dA) {
-    const bf16_t* Ak = P.A + kt * BK;
-    const bf16_t* Wk = P.W + kt * BK;
+  // chunk q = i*NT + tid lands at LDS byte q*16 = (i*NT + wave*64)*16 + lane*16.  Slab indices
+  // past the end are clamped (the copy is redundant but keeps the load count per slab fixed,
+  // which the vmcnt arithmetic below relies on).
+  auto issue = [&](int kt) {
+    unsigned char* dA = smem + (kt % NS) * STAGE;
+    const int ks = (kt < nk ? kt : nk - 1) * BKT;
+    const bf16_t* Ak = P.A + ks;
+    const bf16_t* Wk = P.W + ks;
     unsigned char* dB = dA + OFFB;
 #pragma unroll
     for (int i = 0; i < LA; ++i)
@@ -154,9 +172,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     const unsigned char* pa = st + abase + ((c ^ akey) << 4);
     const unsigned char* pb = st + bbase + ((c ^ bkey) << 4);
 #pragma unroll
-    for (int i = 0; i < TM; ++i) a[i] = *(const bf16x8*)(pa + i * 32 * ROW_BYTES);
+    for (int i = 0; i < TM; ++i) a[i] = *(const bf16x8*)(pa + i * 32 * ROWB);
 #pragma unroll
-    for (int j = 0; j < TN; ++j) b[j] = *(const bf16x8*)(pb + j * 32 * ROW_BYTES);
+    for (int j = 0; j < TN; ++j) b[j] = *(const bf16x8*)(pb + j * 32 * ROWB);
   };
   auto mfma_all = [&](const bf16x8 (&a)[TM], const bf16x8 (&b)[TN]) {
 #pragma unroll
@@ -166,87 +184,45 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
 
-  if constexpr (PIPE == 2) {
-    // probe: the global->LDS traffic of the real loop without MFMA work
-    issue(0, smem);
-    for (int kt = 0; kt < nk; ++kt) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-      __syncthreads();
-      if (kt + 1 < nk) issue(kt + 1, smem + ((kt + 1) & 1) * STAGE);
-    }
-    bf16x8 a[TM], b[TN];
-    load_frags(smem, 0, a, b);
-    mfma_all(a, b);
-  } else if constexpr (PIPE == 3) {
-    // probe: LDS fragment reads + MFMAs of the real loop, global loads for slabs 0 and 1 only
-    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
-    issue(0, smem);
-    issue(nk > 1 ? 1 : 0, smem + STAGE);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    load_frags(smem, 0, a0, b0);
-    for (int kt = 0; kt < nk; ++kt) {
-      const unsigned char* cur = smem + (kt & 1) * STAGE;
-      const unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
+  bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
+#pragma unroll
+  for (int sidx = 0; sidx < NS; ++sidx) issue(sidx);
+  wait_vm<(NS - 1) * LPS, false>();          // slab 0 has landed (mine)
+  __syncthreads();                           // ... and everyone's
+  load_frags(smem, 0, a0, b0);
+  int st_cur = 0;                            // stage of slab kt
+  for (int kt = 0; kt < nk; ++kt) {
+    const unsigned char* cur = smem + st_cur * STAGE;
+    const int st_nxt = st_cur + 1 == NS ? 0 : st_cur + 1;
+    const unsigned char* nxt = smem + st_nxt * STAGE;
+    if (MODE != 2) {
       load_frags(cur, 1, a1, b1);
       mfma_all(a0, b0);
       interleave_hint<TM + TN, TM * TN>();
-      load_frags(cur, 2, a0, b0);
-      mfma_all(a1, b1);
-      interleave_hint<TM + TN, TM * TN>();
-      load_frags(cur, 3, a1, b1);
-      mfma_all(a0, b0);
-      interleave_hint<TM + TN, TM * TN>();
-      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-      __syncthreads();
-      load_frags(nxt, 0, a0, b0);
-      mfma_all(a1, b1);
-      interleave_hint<TM + TN, TM * TN>();
-    }
-  } else if constexpr (PIPE == 0) {
-    // plain loop: one barrier per slab, fragments read right before use
-    issue(0, smem);
-    for (int kt = 0; kt < nk; ++kt) {
-      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // my part of slab kt has landed
-      __syncthreads();                                   // everyone's has; slab kt-1 is free
-      if (kt + 1 < nk) issue(kt + 1, smem + ((kt + 1) & 1) * STAGE);
-      const unsigned char* cur = smem + (kt & 1) * STAGE;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 a[TM], b[TN];
-        load_frags(cur, kk, a, b);
-        mfma_all(a, b);
+      if (KK == 4) {
+        load_frags(cur, 2, a0, b0);
+        mfma_all(a1, b1);
+        interleave_hint<TM + TN, TM * TN>();
+        load_frags(cur, 3, a1, b1);
+        mfma_all(a0, b0);
+        interleave_hint<TM + TN, TM * TN>();
       }
     }
-  } else {
-    bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
-    issue(0, smem);
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // The last fragments of this slab are on their way to registers; slabs kt+1..kt+NS-1 are in
+    // flight.  Wait for slab kt+1 (mine) and my fragments; after the barrier nobody reads `cur`
+    // any more and `nxt` is visible to all.
+    if (MODE == 3) wait_vm<63, true>(); else wait_vm<(NS - 2) * LPS, true>();
     __syncthreads();
-    if (nk > 1) issue(1, smem + STAGE);
-    load_frags(smem, 0, a0, b0);
-    for (int kt = 0; kt < nk; ++kt) {
-      const unsigned char* cur = smem + (kt & 1) * STAGE;
-      const unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
-      load_frags(cur, 1, a1, b1);
-      mfma_all(a0, b0);
-      interleave_hint<TM + TN, TM * TN>();
-      load_frags(cur, 2, a0, b0);
-      mfma_all(a1, b1);
-      interleave_hint<TM + TN, TM * TN>();
-      load_frags(cur, 3, a1, b1);
-      mfma_all(a0, b0);
-      interleave_hint<TM + TN, TM * TN>();
-      // the last fragments of this slab are on their way to registers; slab kt+1 was issued
-      // one slab ago.  After the barrier nobody reads `cur` any more and `nxt` is visible.
-      asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-      __syncthreads();
-      if (kt + 2 < nk) issue(kt + 2, smem + (kt & 1) * STAGE);
-      load_frags(nxt, 0, a0, b0);          // (after the last slab this reads stale LDS; unused)
+    if (MODE != 3) issue(kt + NS);           // into the stage of slab kt
+    if (MODE != 2) {
+      load_frags(nxt, 0, a0, b0);            // (after the last slab this reads a stale stage; unused)
       mfma_all(a1, b1);
       interleave_hint<TM + TN, TM * TN>();
     }
+    st_cur = st_nxt;
   }
+  wait_vm<0, true>();                        // drain the redundant tail loads before LDS is released
+  if (MODE == 2) { load_frags(smem, 1, a1, b1); mfma_all(a1, b1); }
 
   // ---- epilogue ---------------------------------------------------------------------------
   // acc[i][j][e] is C[mb + 8*(e/4) + (e%4)][n]: lanes 0..31 hold 32 consecutive n.
@@ -289,7 +265,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   else epilogue(std::integral_constant<int, OUT_RESID_F32>{});
 }
 
-template <int BM, int BN, int WM, int WN, int PIPE>
+template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE = 0>
 static void launch_t(hipStream_t s, GemmBatch& b) {
   int total = 0;
   for (int i = 0; i < b.n; ++i) {
@@ -301,8 +277,8 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
   }
   b.total_tiles = total;
   if (total == 0) return;
-  size_t lds = 2 * (BM + BN) * ROW_BYTES;
-  auto kern = gemm_kernel<BM, BN, WM, WN, PIPE>;
+  size_t lds = (size_t)NS * (BM + BN) * BKT * 2;
+  auto kern = gemm_kernel<BM, BN, WM, WN, BKT, NS, MODE>;
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -311,29 +287,37 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
   hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), lds, s, b);
 }
 
-// variant codes: BM*1000 + BN; +1000000 = 8 waves (2x4) instead of 4 (2x2);
-// +2000000 = plain (non-pipelined) main loop; 6256256 / 7256256 = measurement probes
+// variant codes: BM*1000 + BN, plus
+//   +1000000  8 waves (2x4) instead of 4 (2x2)
+//   +10000000 k-slab 32 with a 4-stage ring, +20000000 k-slab 32 with a 5-stage ring
+//             (default: k-slab 64, 2 stages)
+//   6256256 / 7256256  measurement probes on the 8-wave 256x256 k-slab-64 kernel
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
-  // Tile choice: the big tile has the best MFMA-per-byte ratio but needs enough tiles to
-  // fill 256 CUs; otherwise fall back to smaller tiles.
+  // Tile choice.  The 256x256 tile (8 waves) halves the L2->LDS traffic per flop of the 128x128
+  // tile and is about 25% faster per tile-flop, but one workgroup fills a CU, so its grid runs
+  // in rounds of 256 tiles: use it when the last round is at least 3/4 full or there are many
+  // rounds; otherwise the 128x128 tile (three workgroups per CU, finer granularity).
   int tile = force_tile;
   if (!tile) {
     long long t256 = 0;
     for (int i = 0; i < b.n; ++i)
       t256 += (long long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
-    tile = (t256 >= 480) ? 1256256 : 128128;
+    const long long rem = t256 % 256;
+    tile = (t256 >= 1024 || (t256 >= 256 && (rem == 0 || rem >= 192))) ? 1256256 : 128128;
   }
   switch (tile) {
-    case 256256: launch_t<256, 256, 2, 2, 1>(s, b); break;
-    case 1256256: launch_t<256, 256, 2, 4, 1>(s, b); break;
-    case 2256256: launch_t<256, 256, 2, 2, 0>(s, b); break;
-    case 3256256: launch_t<256, 256, 2, 4, 0>(s, b); break;
-    case 6256256: launch_t<256, 256, 2, 4, 2>(s, b); break;
-    case 7256256: launch_t<256, 256, 2, 4, 3>(s, b); break;
-    case 256128: launch_t<256, 128, 2, 2, 1>(s, b); break;
-    case 128256: launch_t<128, 256, 2, 2, 1>(s, b); break;
-    case 2128128: launch_t<128, 128, 2, 2, 0>(s, b); break;
-    default: tile = 128128; launch_t<128, 128, 2, 2, 1>(s, b); break;
+    case 256256: launch_t<256, 256, 2, 2, 64, 2>(s, b); break;
+    case 1256256: launch_t<256, 256, 2, 4, 64, 2>(s, b); break;
+    case 10256256: launch_t<256, 256, 2, 2, 32, 4>(s, b); break;
+    case 11256256: launch_t<256, 256, 2, 4, 32, 4>(s, b); break;
+    case 20256256: launch_t<256, 256, 2, 2, 32, 5>(s, b); break;
+    case 21256256: launch_t<256, 256, 2, 4, 32, 5>(s, b); break;
+    case 6256256: launch_t<256, 256, 2, 4, 64, 2, 2>(s, b); break;
+    case 7256256: launch_t<256, 256, 2, 4, 64, 2, 3>(s, b); break;
+    case 256128: launch_t<256, 128, 2, 2, 64, 2>(s, b); break;
+    case 128256: launch_t<128, 256, 2, 2, 64, 2>(s, b); break;
+    case 10128128: launch_t<128, 128, 2, 2, 32, 4>(s, b); break;
+    default: tile = 128128; launch_t<128, 128, 2, 2, 64, 2>(s, b); break;
   }
   return tile;
 }
