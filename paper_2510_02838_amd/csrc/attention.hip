@@ -23,6 +23,7 @@
 // permuted order (bits 2 and 3 of the row index swapped), which makes registers 8s..8s+7
 // of a half-wave hold keys 16s + 8*half + 0..7.
 #include "dit_internal.h"
+#include <cstdlib>
 
 namespace dit {
 
@@ -34,15 +35,27 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 static constexpr int KT = 64;     // keys per tile
 static constexpr int QB = 128;    // queries per workgroup
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+// two floats -> packed bf16 pair, round-to-nearest-even (v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack2bf(float a, float b) {
-  uint32_t ua = __float_as_uint(a), ub = __float_as_uint(b);
-  ua += 0x7FFFu + ((ua >> 16) & 1u);
-  ub += 0x7FFFu + ((ub >> 16) & 1u);
-  return (ua >> 16) | (ub & 0xFFFF0000u);
+  f32x2 v = {a, b};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return *(uint32_t*)&r;
+}
+// value of the other half-wave's lane (lane ^ 32), combined with max / add
+__device__ __forceinline__ float xhalf_max(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float xhalf_sum(float x) {
+  auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
+template <int DH, int OCC>
+__global__ __launch_bounds__(256, OCC) void attn_kernel(const AttnArgs a) {
   constexpr int KROW = DH * 2;                 // bytes per K-tile row
   constexpr int KCPR = DH / 8;                 // 16-byte chunks per K-tile row
   constexpr int KBYTES = KT * KROW;            // K tile
@@ -159,32 +172,36 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
         }
     }
     // ---- online softmax -------------------------------------------------------------------
-    float mx = st[0][0];
+    // The running max is only raised when some row's tile max exceeds it by more than 2^8 in
+    // the exponent (softmax is shift-invariant, so a stale max is exact as long as nothing
+    // overflows: probabilities stay below 2^8); this skips the rescale of O on most tiles.
+    float mx = fmaxf(st[0][0], st[1][0]);
 #pragma unroll
-    for (int t = 0; t < 2; ++t)
+    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(st[0][e], st[1][e]));
+    mx = xhalf_max(mx);
+    if (__builtin_amdgcn_ballot_w64((mx - m_run) * c2 > 8.0f) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
+      m_run = m_new;
+      l_run *= alpha;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) mx = fmaxf(mx, st[t][e]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
-    const float mc = m_new * c2;
-    m_run = m_new;
-    float rs = 0.f;
+      for (int d = 0; d < ND; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[d][e] *= alpha;
+    }
+    const float mc = m_run * c2;
     uint32_t pk[2][8];
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        float p0 = __builtin_amdgcn_exp2f(st[t][e] * c2 - mc);
-        float p1 = __builtin_amdgcn_exp2f(st[t][e + 1] * c2 - mc);
-        rs += p0 + p1;
-        pk[t][e >> 1] = pack2bf(p0, p1);
+        const float p0 = __builtin_amdgcn_exp2f(st[t][e] * c2 - mc);
+        const float p1 = __builtin_amdgcn_exp2f(st[t][e + 1] * c2 - mc);
+        const uint32_t w = pack2bf(p0, p1);
+        pk[t][e >> 1] = w;
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(*(const bf16x2*)&w, ones, l_run, false);  // sum of the rounded values
       }
-    l_run = l_run * alpha + rs;
-#pragma unroll
-    for (int d = 0; d < ND; ++d)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) o[d][e] *= alpha;
     // ---- O^T += V^T P^T -------------------------------------------------------------------
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -201,7 +218,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
   }
 
   // ---- normalise and store -------------------------------------------------------------------
-  const float l_tot = l_run + __shfl_xor(l_run, 32);
+  const float l_tot = xhalf_sum(l_run);
   if (q_ok) {
     const float inv = 1.0f / l_tot;
     const int qrow = qbeg + qi;
@@ -219,10 +236,10 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(const AttnArgs a) {
   }
 }
 
-template <int DH>
+template <int DH, int OCC>
 static void launch_t(hipStream_t s, const AttnArgs& a) {
   constexpr int lds = 2 * (KT * DH * 2 + DH * 128);
-  auto kern = attn_kernel<DH>;
+  auto kern = attn_kernel<DH, OCC>;
   static bool done = false;
   if (!done) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
@@ -233,8 +250,10 @@ static void launch_t(hipStream_t s, const AttnArgs& a) {
 
 void launch_attention(hipStream_t s, const AttnArgs& a) {
   if (a.n_tiles == 0) return;
-  if (a.head_dim == 64) launch_t<64>(s, a);
-  else launch_t<128>(s, a);
+  const char* e = getenv("DIT_ATTN_OCC");
+  const int occ = e ? atoi(e) : 2;
+  if (a.head_dim == 64) { if (occ == 3) launch_t<64, 3>(s, a); else if (occ == 4) launch_t<64, 4>(s, a); else launch_t<64, 2>(s, a); }
+  else launch_t<128, 2>(s, a);
 }
 
 }  // namespace dit
