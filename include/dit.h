@@ -183,7 +183,8 @@ dit_status dit_op_gemm_variant(void* stream, const void* A, int lda, const void*
  * [Nk] rows; vt: dev bf16 [H][dh][ldvt], the transposed values, segment s occupying columns
  * vt_off[s] .. vt_off[s]+len; cu_q / cu_k: host int32 [n_seg+1] prefix sums of query / key
  * rows per segment; vt_off: host int32 [n_seg], multiples of 64, each segment's columns
- * padded to a multiple of 64 with finite values.  o: dev bf16 [Nq][ldo].  `work` is a dev
+ * padded to a multiple of 64 with ZEROS (keys past the end are clamped copies whose
+ * probabilities only cancel against zero values).  o: dev bf16 [Nq][ldo].  `work` is a dev
  * scratch of at least dit_op_attention_work_bytes(...) bytes. */
 size_t     dit_op_attention_work_bytes(int n_seg, const int* cu_q);
 dit_status dit_op_attention(void* stream, const void* q, int ldq, const void* k, int ldk,

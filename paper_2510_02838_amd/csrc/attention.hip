@@ -5,9 +5,9 @@
 // never materialising the score matrix: keys are walked in tiles of 64 with the running
 // max / running sum recurrence in fp32.
 //
-// Work split.  A workgroup of 4 waves owns 128 consecutive queries of one (segment, head);
+// Work split.  A workgroup of 4 (or 8) waves owns 128 (256) consecutive queries of one (segment, head);
 // each wave owns 32 of them.  K tiles [64 keys][dh] and transposed-V tiles [dh][64 keys]
-// stream through a double-buffered LDS ring via direct global->LDS loads.
+// stream through double-buffered LDS tiles via direct global->LDS loads.
 //
 // MFMA formulation (v_mfma_f32_32x32x16_bf16, operands: A = 32 rows x 16 k, B = 16 k x 32
 // cols, a lane supplies 8 consecutive k; result: lane holds column (lane & 31), register e
@@ -23,7 +23,6 @@
 // permuted order (bits 2 and 3 of the row index swapped), which makes registers 8s..8s+7
 // of a half-wave hold keys 16s + 8*half + 0..7.
 #include "dit_internal.h"
-#include <cstdlib>
 
 namespace dit {
 
@@ -33,7 +32,6 @@ typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 static constexpr int KT = 64;     // keys per tile
-static constexpr int QB = 128;    // queries per workgroup
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -54,18 +52,32 @@ __device__ __forceinline__ float xhalf_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int DH, int OCC>
-__global__ __launch_bounds__(256, OCC) void attn_kernel(const AttnArgs a) {
+// max of three.  This file is compiled with -fno-honor-nans, so fmaxf needs no NaN
+// canonicalisation of its inputs and nested calls fold into v_max3_f32.  (Scores are finite:
+// q and k rows are finite and keys past a segment's end are clamped copies of its last key.)
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// Software pipeline of one wave, iteration kt (S = scores, P = exp'd scores):
+//   region B:  S(kt+1) = K(kt+1) Q^T  [MFMA]   overlapped with   P(kt) = exp2(S(kt) - m)  [VALU]
+//   region C:  O += V^T(kt) P(kt)     [MFMA]   overlapped with   row max of S(kt+1)      [VALU]
+// so the matrix pipe and the vector ALU of a SIMD are busy at the same time from ONE wave
+// (two waves of different workgroups on a SIMD fall into lock step and do not overlap by
+// themselves).  K and V^T tiles have separate double buffers: at the barrier of iteration kt
+// K(kt+1) and V(kt) have landed, K(kt+2) and V(kt+1) are issued right after it.
+template <int DH, int NW>
+__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const AttnArgs a) {
+  constexpr int NT = NW * 64;
   constexpr int KROW = DH * 2;                 // bytes per K-tile row
   constexpr int KCPR = DH / 8;                 // 16-byte chunks per K-tile row
   constexpr int KBYTES = KT * KROW;            // K tile
   constexpr int VBYTES = DH * 128;             // V^T tile: DH rows of 64 keys
-  constexpr int STAGE = KBYTES + VBYTES;
-  constexpr int LK = KT * KCPR / 256;          // chunks per thread, K tile
-  constexpr int LV = DH * 8 / 256;             // chunks per thread, V^T tile
+  constexpr int LK = KT * KCPR / NT;          // chunks per thread, K tile
+  constexpr int LV = DH * 8 / NT;             // chunks per thread, V^T tile
   constexpr int ND = DH / 32;                  // output d-tiles
   constexpr int NKK = DH / 16;                 // k-steps of the score product
   extern __shared__ __attribute__((aligned(128))) unsigned char smem[];
+  unsigned char* const sKb = smem;                   // two K tiles
+  unsigned char* const sVb = smem + 2 * KBYTES;      // two V^T tiles
 
   // ---- which (tile, head) ------------------------------------------------------------
   int bid = blockIdx.x;
@@ -96,58 +108,45 @@ __global__ __launch_bounds__(256, OCC) void attn_kernel(const AttnArgs a) {
   int krow[LK];
 #pragma unroll
   for (int i = 0; i < LK; ++i) {
-    int q = i * 256 + tid, r = q / KCPR, pc = q % KCPR;
+    int q = i * NT + tid, r = q / KCPR, pc = q % KCPR;
     int c = (DH == 64) ? (pc ^ ((r >> 1) & 7)) : (pc ^ (r & 15));
     krow[i] = r;
     gk[i] = head * DH + c * 8;
   }
 #pragma unroll
   for (int i = 0; i < LV; ++i) {
-    int q = i * 256 + tid, r = q >> 3, pc = q & 7, c = pc ^ ((r >> 1) & 7);
+    int q = i * NT + tid, r = q >> 3, pc = q & 7, c = pc ^ ((r >> 1) & 7);
     gv[i] = (uint32_t)(head * DH + r) * (uint32_t)a.ldvt + vcol0 + c * 8;
   }
   const int n_kt = (klen + KT - 1) / KT;
-  auto issue = [&](int kt, unsigned char* dst) {
+  auto issue_k = [&](int kt) {
+    unsigned char* dst = sKb + (kt & 1) * KBYTES;
 #pragma unroll
     for (int i = 0; i < LK; ++i) {
       int key = kt * KT + krow[i];
       if (key >= klen) key = klen - 1;      // clamped rows are masked below
       const bf16_t* src = a.k + (size_t)(kbeg + key) * a.ldk + gk[i];
-      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(dst + (i * 256 + wave * 64) * 16), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(dst + (i * NT + wave * 64) * 16), 16, 0, 0);
     }
+  };
+  auto issue_v = [&](int kt) {
+    unsigned char* dst = sVb + (kt & 1) * VBYTES;
     const bf16_t* vsrc = a.vt + kt * KT;
 #pragma unroll
     for (int i = 0; i < LV; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + gv[i]), (lptr_t)(dst + KBYTES + (i * 256 + wave * 64) * 16), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + gv[i]), (lptr_t)(dst + (i * NT + wave * 64) * 16), 16, 0, 0);
   };
 
   // ---- LDS read offsets ------------------------------------------------------------------
   // K operand row rho = l32 reads key kappa(rho): bits 2 and 3 swapped.
   const int kap = (l32 & ~12) | ((l32 & 8) >> 1) | ((l32 & 4) << 1);
-  int koff[2];
-#pragma unroll
-  for (int t = 0; t < 2; ++t) koff[t] = (kap + 32 * t) * KROW;
-  const int kkey0 = (DH == 64) ? ((kap >> 1) & 7) : (kap & 15);   // (+32t does not change it)
-  const int vkey = (l32 >> 1) & 7;                                 // (+32*dt does not change it)
+  const int kkey0 = (DH == 64) ? ((kap >> 1) & 7) : (kap & 15);   // (+32 rows does not change it)
+  const int vkey = (l32 >> 1) & 7;                                 // (+32 rows does not change it)
+  const int koff = kap * KROW, voff = l32 * 128;
 
-  f32x16 o[ND];
-#pragma unroll
-  for (int d = 0; d < ND; ++d)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) o[d][e] = 0.f;
-  float m_run = -INFINITY, l_run = 0.f;
-  const float c2 = a.scale_log2;
-
-  issue(0, smem);
-  for (int kt = 0; kt < n_kt; ++kt) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __syncthreads();
-    if (kt + 1 < n_kt) issue(kt + 1, smem + ((kt + 1) & 1) * STAGE);
-    const unsigned char* sK = smem + (kt & 1) * STAGE;
-    const unsigned char* sV = sK + KBYTES;
-
-    // ---- S^T = K Q^T --------------------------------------------------------------------
-    f32x16 st[2];
+  // S^T tile pair of key tile kt from its K buffer
+  auto scores = [&](int kt, f32x16 (&st)[2]) {
+    const unsigned char* sK = sKb + (kt & 1) * KBYTES + koff;
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -157,28 +156,45 @@ __global__ __launch_bounds__(256, OCC) void attn_kernel(const AttnArgs a) {
       const int c = kk * 2 + half;
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
-        bf16x8 kf = *(const bf16x8*)(sK + koff[t] + ((c ^ kkey0) << 4));
+        bf16x8 kf = *(const bf16x8*)(sK + t * 32 * KROW + ((c ^ kkey0) << 4));
         st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
       }
     }
-    // register e of tile t holds key  kt*64 + 32t + 16*(e/8) + 8*half + e%8
-    if ((kt + 1) * KT > klen) {
+  };
+  auto row_max = [&](const f32x16 (&st)[2]) {      // four independent chains, then combined
+    float m0 = max3(st[0][0], st[0][1], st[0][2]), m1 = max3(st[0][8], st[0][9], st[0][10]);
+    float m2 = max3(st[1][0], st[1][1], st[1][2]), m3 = max3(st[1][8], st[1][9], st[1][10]);
+    m0 = max3(m0, st[0][3], st[0][4]); m1 = max3(m1, st[0][11], st[0][12]);
+    m2 = max3(m2, st[1][3], st[1][4]); m3 = max3(m3, st[1][11], st[1][12]);
+    m0 = max3(m0, st[0][5], st[0][6]); m1 = max3(m1, st[0][13], st[0][14]);
+    m2 = max3(m2, st[1][5], st[1][6]); m3 = max3(m3, st[1][13], st[1][14]);
+    m0 = max3(m0, st[0][7], m1); m2 = max3(m2, st[1][7], m3);
+    return xhalf_max(max3(m0, m2, fmaxf(st[0][15], st[1][15])));
+  };
+
+  f32x16 o[ND];
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+  for (int d = 0; d < ND; ++d)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          int key = kt * KT + 32 * t + 16 * (e >> 3) + 8 * half + (e & 7);
-          if (key >= klen) st[t][e] = -INFINITY;
-        }
-    }
-    // ---- online softmax -------------------------------------------------------------------
-    // The running max is only raised when some row's tile max exceeds it by more than 2^8 in
-    // the exponent (softmax is shift-invariant, so a stale max is exact as long as nothing
+    for (int e = 0; e < 16; ++e) o[d][e] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float c2 = a.scale_log2;
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+
+  // ---- prologue: scores of tile 0 --------------------------------------------------------
+  issue_k(0);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (n_kt > 1) issue_k(1);
+  issue_v(0);
+  f32x16 sc[2], sn[2];
+  scores(0, sc);
+  float mx = row_max(sc);
+
+  for (int kt = 0; kt < n_kt; ++kt) {
+    // ---- (A) raise the running max only when a row's tile max exceeds it by more than 2^8
+    // in the exponent (softmax is shift-invariant, so a stale max is exact as long as nothing
     // overflows: probabilities stay below 2^8); this skips the rescale of O on most tiles.
-    float mx = fmaxf(st[0][0], st[1][0]);
-#pragma unroll
-    for (int e = 1; e < 16; ++e) mx = fmaxf(mx, fmaxf(st[0][e], st[1][e]));
-    mx = xhalf_max(mx);
     if (__builtin_amdgcn_ballot_w64((mx - m_run) * c2 > 8.0f) != 0) {
       const float m_new = fmaxf(m_run, mx);
       const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c2);
@@ -190,19 +206,29 @@ __global__ __launch_bounds__(256, OCC) void attn_kernel(const AttnArgs a) {
         for (int e = 0; e < 16; ++e) o[d][e] *= alpha;
     }
     const float mc = m_run * c2;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // my parts of K(kt+1), V(kt) have landed
+    __syncthreads();                                   // everyone's; K(kt) and V(kt-1) are free
+    if (kt + 2 < n_kt) issue_k(kt + 2);
+    if (kt + 1 < n_kt) issue_v(kt + 1);
+
+    // ---- (B) S(kt+1) on the matrix pipe while P(kt) is exponentiated on the vector ALU.
+    // (After the last tile this multiplies a stale K buffer; the result is not used.  Nothing
+    // between here and the end of (C) branches, so the scheduler sees one region and is left
+    // to interleave the two pipes itself: explicit group hints measured 5-10% slower.)
+    scores(kt + 1, sn);
     uint32_t pk[2][8];
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(st[t][e] * c2 - mc);
-        const float p1 = __builtin_amdgcn_exp2f(st[t][e + 1] * c2 - mc);
+        const float p0 = __builtin_amdgcn_exp2f(sc[t][e] * c2 - mc);
+        const float p1 = __builtin_amdgcn_exp2f(sc[t][e + 1] * c2 - mc);
         const uint32_t w = pack2bf(p0, p1);
         pk[t][e >> 1] = w;
         l_run = __builtin_amdgcn_fdot2_f32_bf16(*(const bf16x2*)&w, ones, l_run, false);  // sum of the rounded values
       }
-    // ---- O^T += V^T P^T -------------------------------------------------------------------
+    // ---- (C) O^T += V^T(kt) P^T(kt) on the matrix pipe while the row max of S(kt+1) is taken
+    const unsigned char* sV = sVb + (kt & 1) * VBYTES + voff;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       union { uint32_t u[4]; bf16x8 v; } pf;
@@ -211,10 +237,30 @@ __global__ __launch_bounds__(256, OCC) void attn_kernel(const AttnArgs a) {
       const int c = 2 * s + half;
 #pragma unroll
       for (int d = 0; d < ND; ++d) {
-        bf16x8 vf = *(const bf16x8*)(sV + (d * 32 + l32) * 128 + ((c ^ vkey) << 4));
+        bf16x8 vf = *(const bf16x8*)(sV + d * 32 * 128 + ((c ^ vkey) << 4));
         o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, o[d], 0, 0, 0);
       }
     }
+    mx = row_max(sn);
+    // Keys past the end of the segment in the last tile are copies of the last key (clamped
+    // loads): they cannot raise the max, and their V^T columns are zero, so O is unaffected;
+    // only their share of the row sum has to be taken out again.
+    // Register e of tile t holds key  kt*64 + 32t + 16*(e/8) + 8*half + e%8.
+    if (kt == n_kt - 1 && (klen & (KT - 1)) != 0) {
+      float corr = 0.f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; e += 2) {
+          const int key = kt * KT + 32 * t + 16 * (e >> 3) + 8 * half + (e & 7);
+          const uint32_t msk = (key >= klen ? 0x3F80u : 0u) | (key + 1 >= klen ? 0x3F800000u : 0u);
+          const uint32_t w = pk[t][e >> 1];
+          corr = __builtin_amdgcn_fdot2_f32_bf16(*(const bf16x2*)&w, *(const bf16x2*)&msk, corr, false);
+        }
+      l_run -= corr;
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) sc[t] = sn[t];
   }
 
   // ---- normalise and store -------------------------------------------------------------------
@@ -236,24 +282,25 @@ __global__ __launch_bounds__(256, OCC) void attn_kernel(const AttnArgs a) {
   }
 }
 
-template <int DH, int OCC>
+template <int DH, int NW>
 static void launch_t(hipStream_t s, const AttnArgs& a) {
-  constexpr int lds = 2 * (KT * DH * 2 + DH * 128);
-  auto kern = attn_kernel<DH, OCC>;
+  constexpr int lds = 2 * (KT * DH * 2 + DH * 128);   // two K tiles + two V^T tiles
+  auto kern = attn_kernel<DH, NW>;
   static bool done = false;
   if (!done) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.n_heads), dim3(256), lds, s, a);
+  hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.n_heads), dim3(NW * 64), lds, s, a);
 }
 
 void launch_attention(hipStream_t s, const AttnArgs& a) {
   if (a.n_tiles == 0) return;
-  const char* e = getenv("DIT_ATTN_OCC");
-  const int occ = e ? atoi(e) : 2;
-  if (a.head_dim == 64) { if (occ == 3) launch_t<64, 3>(s, a); else if (occ == 4) launch_t<64, 4>(s, a); else launch_t<64, 2>(s, a); }
-  else launch_t<128, 2>(s, a);
+  if (a.q_per_tile == 256) {
+    if (a.head_dim == 64) launch_t<64, 8>(s, a); else launch_t<128, 8>(s, a);
+  } else {
+    if (a.head_dim == 64) launch_t<64, 4>(s, a); else launch_t<128, 4>(s, a);
+  }
 }
 
 }  // namespace dit

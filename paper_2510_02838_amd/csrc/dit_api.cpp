@@ -10,12 +10,20 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <cstdlib>
 #include <map>
 #include <string>
 #include <unordered_map>
 #include <vector>
 
 using namespace dit;
+
+namespace dit {
+int attn_q_per_tile() {
+  static const int v = [] { const char* e = getenv("DIT_ATTN_QB"); return e && atoi(e) == 256 ? 256 : 128; }();
+  return v;
+}
+}  // namespace dit
 
 namespace {
 
@@ -281,8 +289,8 @@ void build_plan(const dit_ctx* c, int n_req, const dit_req* reqs, Plan& P) {
       src_of_col_j[P.vt_off[r] + t] = P.cu_joint[r] + t;
     }
     for (int t = 0; t < nt; ++t) src_of_col_x[P.vtx_off[r] + t] = P.cu_txt[r] + t;
-    for (int q0 = 0; q0 < nj; q0 += 128) P.tiles.push_back(AttnTile{r, q0});
-    for (int q0 = 0; q0 < ni; q0 += 128) P.xtiles.push_back(AttnTile{r, q0});
+    for (int q0 = 0; q0 < nj; q0 += attn_q_per_tile()) P.tiles.push_back(AttnTile{r, q0});
+    for (int q0 = 0; q0 < ni; q0 += attn_q_per_tile()) P.xtiles.push_back(AttnTile{r, q0});
   }
   // longest key ranges first, so that the tail of the grid is made of short tiles
   std::stable_sort(P.tiles.begin(), P.tiles.end(), [&](const AttnTile& a, const AttnTile& b) {
@@ -422,7 +430,7 @@ void run_attention(dit_ctx* c, const Run& R, const bf16_t* q, int ldq, const bf1
   AttnArgs a;
   a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.ldvt = ldvt; a.o = o; a.ldo = ldo;
   a.n_heads = g.n_heads; a.head_dim = g.head_dim; a.cu_q = cu_q; a.cu_k = cu_k; a.vt_off = vt_off;
-  a.tiles = tiles; a.n_tiles = n_tiles; a.o_row_map = o_row_map;
+  a.tiles = tiles; a.n_tiles = n_tiles; a.o_row_map = o_row_map; a.q_per_tile = attn_q_per_tile();
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
   Scope sc(c, DIT_PROF_ATTN, flop_units * g.hidden, 0);
   launch_attention(c->stream, a);
@@ -972,7 +980,7 @@ dit_status dit_op_gemm_variant(void* stream, const void* A, int lda, const void*
 size_t dit_op_attention_work_bytes(int n_seg, const int* cu_q) {
   if (n_seg <= 0 || !cu_q) return 0;
   size_t tiles = 0;
-  for (int s = 0; s < n_seg; ++s) tiles += (size_t)(cu_q[s + 1] - cu_q[s] + 127) / 128;
+  for (int s = 0; s < n_seg; ++s) tiles += (size_t)(cu_q[s + 1] - cu_q[s] + 127) / 128;   // upper bound for either tile size
   return rup((size_t)(n_seg + 1) * 4, 256) * 2 + rup((size_t)n_seg * 4, 256) + rup(tiles * sizeof(AttnTile), 256);
 }
 
@@ -988,7 +996,7 @@ dit_status dit_op_attention(void* stream, const void* q, int ldq, const void* k,
     const int nq = cu_q[s + 1] - cu_q[s], nk = cu_k[s + 1] - cu_k[s];
     if (nq < 0 || nk <= 0 || vt_off[s] % 64 || vt_off[s] < 0) return DIT_ESHAPE;
     if (vt_off[s] + (int)rup(nk, 64) > ldvt) return DIT_ESHAPE;
-    for (int q0 = 0; q0 < nq; q0 += 128) tiles.push_back(AttnTile{s, q0});
+    for (int q0 = 0; q0 < nq; q0 += attn_q_per_tile()) tiles.push_back(AttnTile{s, q0});
   }
   if (work_bytes < dit_op_attention_work_bytes(n_seg, cu_q)) return DIT_ENOMEM;
   std::stable_sort(tiles.begin(), tiles.end(), [&](const AttnTile& a, const AttnTile& b) {
@@ -1008,6 +1016,7 @@ dit_status dit_op_attention(void* stream, const void* q, int ldq, const void* k,
   a.o = (bf16_t*)o; a.ldo = ldo; a.n_heads = n_heads; a.head_dim = head_dim;
   a.cu_q = (const int*)w; a.cu_k = (const int*)(w + cu_b); a.vt_off = (const int*)(w + 2 * cu_b);
   a.tiles = (const AttnTile*)(w + 2 * cu_b + vo_b); a.n_tiles = (int)tiles.size(); a.o_row_map = nullptr;
+  a.q_per_tile = attn_q_per_tile();
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
   launch_attention(s, a);
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;

@@ -26,7 +26,8 @@ struct GemmBatch { int n; int total_tiles; GemmProblem p[3]; };
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile = 0);
 
 // ---- attention ----------------------------------------------------------------------
-struct AttnTile { int seg; int q0; };   // one block of 128 queries of one segment
+struct AttnTile { int seg; int q0; };   // one block of q_per_tile queries of one segment
+int attn_q_per_tile();                  // 128 or 256: queries per workgroup (tuning knob)
 struct AttnArgs {
   const bf16_t* q; int ldq;
   const bf16_t* k; int ldk;
@@ -35,6 +36,7 @@ struct AttnArgs {
   int n_heads, head_dim;
   const int* cu_q; const int* cu_k; const int* vt_off;   // device
   const AttnTile* tiles; int n_tiles;                    // device
+  int q_per_tile;                                        // 128 (4 waves) or 256 (8 waves)
   // optional scatter of output rows: row j of segment s goes to o_row = map(...)
   const int* o_row_map;         // device [Nq] or null (identity)
   float scale_log2;             // log2(e)/sqrt(dh)
