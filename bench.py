@@ -20,6 +20,10 @@ sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
+# Fabric-side bytes per GEMM launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scale
+# factors from the streaming calibration kernel), averaged over the GEMM launches of a step;
+# measured once per workload, see profiles/<workload>_hbm_traffic.txt.  None = not measured.
+MEASURED_GEMM_TRAFFIC_BYTES = {"sd3": 224e6}
 
 
 def cpu_baseline(name, arch, reqs):
@@ -64,6 +68,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--workload", default="sd3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run the streaming update kernel on 2^26 floats (reads 512 MiB, writes "
+                         "256 MiB): a kernel of known traffic to scale rocprofv3 FETCH_SIZE/WRITE_SIZE by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus above 1 is not supported "
@@ -94,6 +101,13 @@ def main():
     def sig(T):
         return np.stack([synth.default_sigmas(T, s) for s in shifts])
 
+    if args.calibrate_copy:
+        n = 1 << 26
+        ca, cb = torch.zeros(n, device="cuda"), torch.ones(n, device="cuda")
+        for _ in range(3):
+            assert B.dit_op_latent_update(None, ca.data_ptr(), cb.data_ptr(), n, 1.0, 0.5) == 0
+        torch.cuda.synchronize()
+        del ca, cb
     x = x0.clone()
     if W > 0:
         m.sample(reqs, x, d_cond, sig(W))
@@ -134,7 +148,9 @@ def main():
                    "steps_per_sample": K, "finite": finite},
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel (bf16 MFMA GEMM, all launches of the step)",
                      "achieved": gemm_tf, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": gemm_tf / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": gemm_tf / PEAK_BF16_TFLOPS, "traffic": MEASURED_GEMM_TRAFFIC_BYTES.get(name),
+                     "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, scaled)",
+                     "algorithmic_bytes_per_launch": g["bytes"] / max(g["launches"], 1),
                      "avg_launch_us": g["ms"] / max(g["launches"], 1) * 1e3,
                      "flop_per_launch": g["flop"] / max(g["launches"], 1)},
         "mfma": {"gemm_tflops": gemm_tf, "gemm_frac_peak": gemm_tf / PEAK_BF16_TFLOPS,
