@@ -333,8 +333,13 @@ class DiTOracle:
         tap(p + ".x_out", x)
         return x
 
-    def _w_block(self, p, x, cproj, e_base, pos, tap):
-        """Self-attention, cross-attention to the projected condition, MLP."""
+    def _w_block(self, p, x, cproj, e_base, pos, tap, rows=None):
+        """Self-attention, cross-attention to the projected condition, MLP.
+
+        rows: optional index array.  Keys and values are still formed from every token, but the
+        query side and everything after it are evaluated for these tokens only and only their
+        rows are returned (the same formulas on fewer rows; used on the last block of a model
+        whose full score matrix is too large for the CPU)."""
         d = self.arch["hidden"]
         H = self.arch["n_heads"]
         e = self._w(p + ".mod_table") + e_base.reshape(6, d)
@@ -343,6 +348,8 @@ class DiTOracle:
         qkv = self._lin(h, p + ".qkv")
         q, k, v = qkv[:, :d], qkv[:, d:2 * d], qkv[:, 2 * d:]
         q, k = self._qk_norm_rope(q, k, p + ".", pos)
+        if rows is not None:
+            q, x = q[rows], x[rows]
         o = multi_head_attention(q, k, v, H)
         tap(p + ".attn", o)
         x = x + g1 * self._lin(o, p + ".proj")
@@ -412,6 +419,32 @@ class DiTOracle:
         y = self._lin(modulate(xi, mod[:d], mod[d:]), "final")
         tap("final", y)
         return unpatchify(y, latent.shape, a["patch"])
+
+    def final_rows_w(self, latent, cond, sigma, rows, taps=None):
+        """Family W only: the final layer's output rows (before unpatchify) for the image tokens
+        `rows`, with the LAST block evaluated for those query rows only (see `_w_block`).  For a
+        one-block model this is exact at any token count."""
+        a = self.arch
+        assert a["family"] == "W"
+        d = a["hidden"]
+        pt, ph, pw = a["patch"]
+        latent = np.asarray(latent, dtype=F64)
+        cond = np.asarray(cond, dtype=F64)
+        _, f, h, w = latent.shape
+        m = self.conditioning(sigma)
+        xi = self._lin(patchify(latent, a["patch"]), "x_embed")
+        xt = self._lin(cond, "c_embed")
+        pos_i = token_positions(f // pt, h // ph, w // pw)
+        e_base = self._lin(m, "t_proj")
+        nb = a["n_blocks"]
+        for l in range(nb):
+            def tap(name, val, last=(l == nb - 1)):
+                if taps is not None and last:
+                    taps[name] = np.array(val, dtype=F64, copy=True)
+            xi = self._w_block(f"blk{l}", xi, xt, e_base, pos_i, tap,
+                               rows=rows if l == nb - 1 else None)
+        mod = self._lin(m, "final.mod")
+        return self._lin(modulate(xi, mod[:d], mod[d:]), "final")
 
     # -- Phi and the loop ---------------------------------------------------------------
     def step(self, latent, cond, sigma_cur, sigma_next, kind=0, taps=None):

@@ -348,7 +348,7 @@ void layout_ws(const dit_ctx* c, const Plan& P, int max_steps, WsLayout& L) {
   L.o = take(Ns * d * 2);
   L.act = take(std::max(Ns * dff, std::max(Nj * wide, Nt * 2 * d)) * 2);
   L.cproj = take(g.family == DIT_FAMILY_W ? Nt * d * 2 : 0);
-  L.patch = take(Ni * (size_t)L.ldp * 2);
+  L.patch = take(Ni * (size_t)L.ldp * 2 * 2);   // hi and lo terms
   L.yfin = take(Ni * (size_t)L.ldy * 4);
   L.rope = take((g.rope_axes[0] + g.rope_axes[1] + g.rope_axes[2]) > 0 ? Nj * (g.head_dim / 2) * 8 : 0);
   L.total = o;
@@ -679,10 +679,14 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
     {
       Scope sc(c, DIT_PROF_OTHER, 0, 0);
       launch_patchify(s, latents, (const long long*)(c->ws + L.meta + P.o_lat_off), (const int4*)(c->ws + L.meta + P.o_req_dims),
-                      tok, Ni, g.latent_ch, g.patch_t, g.patch_h, g.patch_w, R.at<bf16_t>(L.patch), L.ldp);
+                      tok, Ni, g.latent_ch, g.patch_t, g.patch_h, g.patch_w, R.at<bf16_t>(L.patch),
+                      R.at<bf16_t>(L.patch) + (size_t)Ni * L.ldp, L.ldp);
       if (P.has_txt_stream) launch_copy_rows_f32(s, R.at<float>(L.xt0), nullptr, x, nullptr, Nt, d);
     }
+    // The latent enters as two bf16 terms (hi + lo) so that the embedding sees it to ~16 bits:
+    // with small weights the model output is dominated by this path and by the final layer.
     run_gemm(c, {mk(R.at<bf16_t>(L.patch), L.ldp, Wm(c, "x_embed.w"), Wld(c, "x_embed.w"), Wv(c, "x_embed.b"), Ni, d, L.ldp, OUT_F32, x_img, d)});
+    run_gemm(c, {mk(R.at<bf16_t>(L.patch) + (size_t)Ni * L.ldp, L.ldp, Wm(c, "x_embed.w"), Wld(c, "x_embed.w"), nullptr, Ni, d, L.ldp, OUT_RESID_F32, x_img, d)});
     if (g.family == DIT_FAMILY_J) {
       Scope sc(c, DIT_PROF_OTHER, 0, 0);
       launch_add_pe(s, x_img, tok, Ni, d);
@@ -717,9 +721,11 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
     bf16_t* h = R.at<bf16_t>(L.h);
     {
       Scope sc(c, DIT_PROF_LNMOD, 0, 6.0 * Ni * d);
-      launch_ln_modulate(s, x_img, h, Ni, d, mf, mf + d, MC, R.ip(P.o_row_req_s) + soff_img, nullptr, nullptr);
+      launch_ln_modulate(s, x_img, h, Ni, d, mf, mf + d, MC, R.ip(P.o_row_req_s) + soff_img, nullptr, nullptr,
+                         R.at<bf16_t>(L.o));     // second term in the (free) attention-output buffer
     }
     run_gemm(c, {mk(h, d, Wm(c, "final.w"), Wld(c, "final.w"), Wv(c, "final.b"), Ni, c->pdim, d, OUT_F32, R.at<float>(L.yfin), L.ldy)});
+    run_gemm(c, {mk(R.at<bf16_t>(L.o), d, Wm(c, "final.w"), Wld(c, "final.w"), nullptr, Ni, c->pdim, d, OUT_RESID_F32, R.at<float>(L.yfin), L.ldy)});
     TAP("final", R.at<float>(L.yfin), Ni, c->pdim, 4, L.ldy);
     {
       Scope sc(c, DIT_PROF_UPDATE, 0, 12.0 * P.lat_total);
@@ -1026,7 +1032,7 @@ dit_status dit_op_ln_modulate(void* stream, const float* x, void* y, int M, int 
                               const float* scale, int mod_stride, const int* row_req) {
   if (!x || !y || !shift || !scale) return DIT_EINVAL;
   if (M < 0 || d <= 0 || d % 256 || d > 5120) return DIT_ESHAPE;
-  launch_ln_modulate((hipStream_t)stream, x, (bf16_t*)y, M, d, shift, scale, mod_stride, row_req, nullptr, nullptr);
+  launch_ln_modulate((hipStream_t)stream, x, (bf16_t*)y, M, d, shift, scale, mod_stride, row_req, nullptr, nullptr, nullptr);
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }
 

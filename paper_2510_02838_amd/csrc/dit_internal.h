@@ -46,7 +46,8 @@ void launch_attention(hipStream_t s, const AttnArgs& a);
 // ---- row-wise / elementwise ---------------------------------------------------------
 void launch_ln_modulate(hipStream_t s, const float* x, bf16_t* y, int M, int d,
                         const float* shift, const float* scale, int mod_stride,
-                        const int* row_req, const float* gain, const float* beta);
+                        const int* row_req, const float* gain, const float* beta,
+                        bf16_t* y_lo = nullptr);   // y_lo: optional second bf16 term (value - y)
 
 // q/k per-head RMS norm (+ rotary) from a [M][ld] bf16 matrix holding q at column 0, k at
 // column d; writes rows to qo/ko at row dst_row[m] (or m).  rope: [n_dst_rows][dh/2] (cos,sin)
@@ -76,7 +77,7 @@ struct TokInfo { int req; int f, i, j; };  // per image token: request and grid 
 void launch_patchify(hipStream_t s, const float* lat, const long long* lat_off_dev,
                      const int4* req_dims_dev /* (F,H,W,unused) per req */,
                      const TokInfo* tok, int n_img, int C, int pt, int ph, int pw,
-                     bf16_t* out, int ldp);
+                     bf16_t* out, bf16_t* out_lo, int ldp);   // out + out_lo = latent to ~16 bits
 // x[m][c] += PE(i,j)[c] for family J
 void launch_add_pe(hipStream_t s, float* x, const TokInfo* tok, int n_img, int d);
 // unpatchify + update: for every latent element: v = y[token][feat]; x = a x + b v

@@ -30,7 +30,8 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
                                                           const float* __restrict__ scale, int mod_stride,
                                                           const int* __restrict__ row_req,
                                                           const float* __restrict__ gain,
-                                                          const float* __restrict__ beta) {
+                                                          const float* __restrict__ beta,
+                                                          bf16_t* __restrict__ y_lo) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= M) return;
   const int lane = threadIdx.x & 63;
@@ -67,21 +68,29 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
     if (i < nv) {
       float4 a = sc[i * 64 + lane], b = sh[i * 64 + lane];
       if (plus_one) { a.x += 1.f; a.y += 1.f; a.z += 1.f; a.w += 1.f; }
+      const float r0 = v[i].x * rstd * a.x + b.x, r1 = v[i].y * rstd * a.y + b.y;
+      const float r2 = v[i].z * rstd * a.z + b.z, r3 = v[i].w * rstd * a.w + b.w;
       uint2 w;
-      w.x = pack2(v[i].x * rstd * a.x + b.x, v[i].y * rstd * a.y + b.y);
-      w.y = pack2(v[i].z * rstd * a.z + b.z, v[i].w * rstd * a.w + b.w);
+      w.x = pack2(r0, r1);
+      w.y = pack2(r2, r3);
       yr[i * 64 + lane] = w;
+      if (y_lo) {   // second bf16 term: value = hi + lo to about 16 mantissa bits
+        uint2 l;
+        l.x = pack2(r0 - bf2f((uint16_t)(w.x & 0xFFFF)), r1 - bf2f((uint16_t)(w.x >> 16)));
+        l.y = pack2(r2 - bf2f((uint16_t)(w.y & 0xFFFF)), r3 - bf2f((uint16_t)(w.y >> 16)));
+        ((uint2*)(y_lo + (size_t)row * d))[i * 64 + lane] = l;
+      }
     }
 }
 
 void launch_ln_modulate(hipStream_t s, const float* x, bf16_t* y, int M, int d, const float* shift,
                         const float* scale, int mod_stride, const int* row_req, const float* gain,
-                        const float* beta) {
+                        const float* beta, bf16_t* y_lo) {
   if (M == 0) return;
   dim3 g((M + 3) / 4), b(256);
-  if (d <= 1024) hipLaunchKernelGGL(ln_modulate_kernel<4>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta);
-  else if (d <= 3072) hipLaunchKernelGGL(ln_modulate_kernel<12>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta);
-  else hipLaunchKernelGGL(ln_modulate_kernel<20>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta);
+  if (d <= 1024) hipLaunchKernelGGL(ln_modulate_kernel<4>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo);
+  else if (d <= 3072) hipLaunchKernelGGL(ln_modulate_kernel<12>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo);
+  else hipLaunchKernelGGL(ln_modulate_kernel<20>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -253,7 +262,8 @@ __global__ __launch_bounds__(256) void patchify_kernel(const float* __restrict__
                                                        const long long* __restrict__ lat_off,
                                                        const int4* __restrict__ req_dims,
                                                        const TokInfo* __restrict__ tok, int n_img, int C,
-                                                       int pt, int ph, int pw, bf16_t* __restrict__ out, int ldp) {
+                                                       int pt, int ph, int pw, bf16_t* __restrict__ out,
+                                                       bf16_t* __restrict__ out_lo, int ldp) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   if (idx >= (long long)n_img * ldp) return;
   const int t = (int)(idx / ldp), feat = (int)(idx % ldp);
@@ -268,14 +278,17 @@ __global__ __launch_bounds__(256) void patchify_kernel(const float* __restrict__
     const int f = ti.f * pt + dt, yy = ti.i * ph + dh, xx = ti.j * pw + dw;
     v = lat[lat_off[ti.req] + (((long long)c * dm.x + f) * dm.y + yy) * dm.z + xx];
   }
-  out[idx] = f2bf(v);
+  const uint16_t hi = f2bf(v);
+  out[idx] = hi;
+  out_lo[idx] = f2bf(v - bf2f(hi));     // latent = hi + lo to about 16 mantissa bits
 }
 void launch_patchify(hipStream_t s, const float* lat, const long long* lat_off_dev, const int4* req_dims_dev,
-                     const TokInfo* tok, int n_img, int C, int pt, int ph, int pw, bf16_t* out, int ldp) {
+                     const TokInfo* tok, int n_img, int C, int pt, int ph, int pw, bf16_t* out, bf16_t* out_lo,
+                     int ldp) {
   const long long total = (long long)n_img * ldp;
   if (total == 0) return;
   hipLaunchKernelGGL(patchify_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, lat, lat_off_dev,
-                     req_dims_dev, tok, n_img, C, pt, ph, pw, out, ldp);
+                     req_dims_dev, tok, n_img, C, pt, ph, pw, out, out_lo, ldp);
 }
 
 // x[t][c] += PE(i, j)[c]:  quarters [sin(i w), cos(i w), sin(j w), cos(j w)], w_k = 1e4^(-k/(d/4))

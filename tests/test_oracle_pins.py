@@ -481,3 +481,14 @@ def test_tiny_config_regression_file():
     assert np.array_equal(tab[:, 0].astype(int), idx)
     assert np.allclose(tab[:, 1], v0, rtol=0, atol=1e-12)
     assert np.allclose(tab[:, 2], x0, rtol=0, atol=1e-12)
+
+
+def test_row_sampled_last_block_equals_full_evaluation():
+    """The row-restricted evaluation of the last block is the full evaluation on those rows."""
+    arch = small_arch("W", n_blocks=2)
+    m = O.DiTOracle(arch, rand_params(arch))
+    lat, cond = rand_io(arch, f=2, h=4, w=6)
+    taps = {}
+    m.velocity(lat, cond, 0.5, taps)
+    rows = np.array([0, 3, 7, 11])
+    assert np.allclose(m.final_rows_w(lat, cond, 0.5, rows), taps["final"][rows], atol=1e-12)
