@@ -966,6 +966,7 @@ dit_status dit_op_gemm(void* stream, const void* A, int lda, const void* W, int 
   if (M < 0 || N < 0 || K <= 0 || K % 64 || lda < K || ldw < K || ldc < N) return DIT_ESHAPE;
   if (lda % 8 || ldw % 8) return DIT_ESHAPE;
   if (out_kind < 0 || out_kind > 3) return DIT_EINVAL;
+  if (ldc % ((out_kind == 1 || out_kind == 3) ? 4 : 8) || ((uintptr_t)out & 15)) return DIT_ESHAPE;
   if (M == 0 || N == 0) return DIT_OK;
   GemmBatch b; b.n = 1; b.total_tiles = 0;
   b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc, gate, gate_stride, row_req);
@@ -977,6 +978,8 @@ dit_status dit_op_gemm_variant(void* stream, const void* A, int lda, const void*
                                int N, int K, int out_kind, void* out, int ldc, int variant) {
   if (!A || !W || !out) return DIT_EINVAL;
   if (M <= 0 || N <= 0 || K <= 0 || K % 64 || lda < K || ldw < K || ldc < N) return DIT_ESHAPE;
+  if (out_kind < 0 || out_kind > 2) return DIT_EINVAL;
+  if (lda % 8 || ldw % 8 || ldc % (out_kind == 1 ? 4 : 8) || ((uintptr_t)out & 15)) return DIT_ESHAPE;
   GemmBatch b; b.n = 1; b.total_tiles = 0;
   b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc);
   launch_gemm((hipStream_t)stream, b, variant);

@@ -45,6 +45,16 @@ __device__ __forceinline__ uint16_t f2bf(float f) {
   return (uint16_t)(u >> 16);
 }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// two floats -> packed bf16 pair, round-to-nearest-even (v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack2bf(float a, float b) {
+  f32x2 v = {a, b};
+  bf16x2 r = __builtin_convertvector(v, bf16x2);
+  return *(uint32_t*)&r;
+}
+
 __device__ __forceinline__ float gelu_tanh(float x) {
   // 0.5 x (1 + tanh(u)) == x * sigmoid(2u),  u = sqrt(2/pi) (x + 0.044715 x^3)
   float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
@@ -96,7 +106,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 
   // ---- workgroup -> (problem, tile) ----------------------------------------------------
   int bid = blockIdx.x, nb = gridDim.x;
-  {
+  if (MODE != 5) {
     int x = bid & 7, idx = bid >> 3, q = nb >> 3, rem = nb & 7;
     bid = x * q + (x < rem ? x : rem) + idx;
   }
@@ -184,6 +194,50 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
 
+  if constexpr (MODE == 4) {
+    // probe: the same global reads into registers (no LDS), two slabs in flight
+    u32x4 r0[LPS], r1[LPS], sink = {0, 0, 0, 0};
+    auto rd = [&](int kt, u32x4 (&r)[LPS]) {
+      const int ks = (kt < nk ? kt : nk - 1) * BKT;
+#pragma unroll
+      for (int i = 0; i < LA; ++i) r[i] = *(const u32x4*)(P.A + ks + ga[i]);
+#pragma unroll
+      for (int i = 0; i < LB; ++i) r[LA + i] = *(const u32x4*)(P.W + ks + gb[i]);
+    };
+    rd(0, r0);
+    for (int kt = 0; kt < nk; kt += 2) {
+      rd(kt + 1, r1);
+#pragma unroll
+      for (int i = 0; i < LPS; ++i) sink ^= r0[i];
+      rd(kt + 2, r0);
+#pragma unroll
+      for (int i = 0; i < LPS; ++i) sink ^= r1[i];
+    }
+    acc[0][0][0] = __uint_as_float(sink[0] ^ sink[1] ^ sink[2] ^ sink[3]);
+  } else if constexpr (MODE == 6) {
+    // probe: global -> registers -> ds_write_b128 into the ring, one slab in flight, one barrier
+    // per slab (the traffic pattern of MODE 2 without the LDS-DMA path)
+    u32x4 r[LPS];
+    auto rd = [&](int kt) {
+      const int ks = (kt < nk ? kt : nk - 1) * BKT;
+#pragma unroll
+      for (int i = 0; i < LA; ++i) r[i] = *(const u32x4*)(P.A + ks + ga[i]);
+#pragma unroll
+      for (int i = 0; i < LB; ++i) r[LA + i] = *(const u32x4*)(P.W + ks + gb[i]);
+    };
+    rd(0);
+    for (int kt = 0; kt < nk; ++kt) {
+      unsigned char* dA = smem + (kt % NS) * STAGE;
+#pragma unroll
+      for (int i = 0; i < LA; ++i) *(u32x4*)(dA + (i * NT + tid) * 16) = r[i];
+#pragma unroll
+      for (int i = 0; i < LB; ++i) *(u32x4*)(dA + OFFB + (i * NT + tid) * 16) = r[LA + i];
+      __syncthreads();
+      rd(kt + 1);
+    }
+    bf16x8 a1[TM], b1[TN];
+    load_frags(smem, 1, a1, b1); mfma_all(a1, b1);
+  } else {
   bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
 #pragma unroll
   for (int sidx = 0; sidx < NS; ++sidx) issue(sidx);
@@ -195,7 +249,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     const unsigned char* cur = smem + st_cur * STAGE;
     const int st_nxt = st_cur + 1 == NS ? 0 : st_cur + 1;
     const unsigned char* nxt = smem + st_nxt * STAGE;
-    if (MODE != 2) {
+    if (MODE != 2 && MODE != 5) {
       load_frags(cur, 1, a1, b1);
       mfma_all(a0, b0);
       interleave_hint<TM + TN, TM * TN>();
@@ -211,10 +265,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     // The last fragments of this slab are on their way to registers; slabs kt+1..kt+NS-1 are in
     // flight.  Wait for slab kt+1 (mine) and my fragments; after the barrier nobody reads `cur`
     // any more and `nxt` is visible to all.
-    if (MODE == 3) wait_vm<63, true>(); else wait_vm<(NS - 2) * LPS, true>();
-    __syncthreads();
-    if (MODE != 3) issue(kt + NS);           // into the stage of slab kt
-    if (MODE != 2) {
+    if (MODE == 3 || MODE == 7) wait_vm<63, true>(); else wait_vm<(NS - 2) * LPS, true>();
+    if (MODE != 7) __syncthreads();
+    if (MODE != 3 && MODE != 7) issue(kt + NS);           // into the stage of slab kt
+    if (MODE != 2 && MODE != 5) {
       load_frags(nxt, 0, a0, b0);            // (after the last slab this reads a stale stage; unused)
       mfma_all(a1, b1);
       interleave_hint<TM + TN, TM * TN>();
@@ -222,41 +276,91 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     st_cur = st_nxt;
   }
   wait_vm<0, true>();                        // drain the redundant tail loads before LDS is released
-  if (MODE == 2) { load_frags(smem, 1, a1, b1); mfma_all(a1, b1); }
+  if (MODE == 2 || MODE == 5) { load_frags(smem, 1, a1, b1); mfma_all(a1, b1); }
+  }
 
   // ---- epilogue ---------------------------------------------------------------------------
-  // acc[i][j][e] is C[mb + 8*(e/4) + (e%4)][n]: lanes 0..31 hold 32 consecutive n.
+  // acc[i][j][e] is C[32i + 8*(e/4) + 4*half + e%4][32j + lane%32] of the wave's sub-tile: a lane
+  // holds one column, so direct stores would be 2- or 4-byte pieces.  Each wave therefore turns
+  // its sub-tile 32 rows at a time through a private LDS patch (row stride TN*128 + 32 bytes:
+  // the two half-waves, 4 rows apart, then fall into disjoint bank halves) and reads it back
+  // row-major, 4 (fp32 out) or 8 (bf16 out) consecutive columns per lane: global accesses are
+  // 16 bytes per lane and whole rows of the sub-tile per instruction.
+  __syncthreads();     // every wave's ring loads have landed and all fragment reads are done
+  constexpr int RS = TN * 128 + 32;
+  unsigned char* stg = smem + wave * (32 * RS);
+  static_assert(WM * WN * 32 * RS <= NS * STAGE, "staging patch fits the ring");
   auto epilogue = [&](auto kind_tag) {
     constexpr int KIND = decltype(kind_tag)::value;
+    constexpr bool F32OUT = KIND == OUT_F32 || KIND == OUT_RESID_F32;
+    constexpr int VEC = F32OUT ? 4 : 8;          // columns per lane
+    constexpr int LPR = TN * 32 / VEC;           // lanes per row
+    constexpr int RPI = 64 / LPR;                // rows per instruction
+    const int lr = lane / LPR, lc = (lane % LPR) * VEC;
+    const int n = n0 + wn * (BN / WN) + lc;      // first of this lane's columns
+    const bool full = n + VEC <= P.N;
+    float bv[VEC];
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int n = n0 + wn * (BN / WN) + j * 32 + (lane & 31);
-      if (n < P.N) {
-        const float bv = P.bias ? P.bias[n] : 0.f;
+    for (int c = 0; c < VEC; ++c) bv[c] = (P.bias && n + c < P.N) ? P.bias[n + c] : 0.f;
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-          const int mb = m0 + wm * (BM / WM) + i * 32 + 4 * half;
+    for (int i = 0; i < TM; ++i) {
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int m = mb + 8 * (e >> 2) + (e & 3);
-            if (m < P.M) {
-              float v = acc[i][j][e] + bv;
-              const size_t o = (size_t)m * P.ldc + n;
-              if (KIND == OUT_BF16) {
-                ((bf16_t*)P.out)[o] = f2bf(v);
-              } else if (KIND == OUT_F32) {
-                ((float*)P.out)[o] = v;
-              } else if (KIND == OUT_GELU_BF16) {
-                ((bf16_t*)P.out)[o] = f2bf(gelu_tanh(v));
-              } else {
-                float g = 1.f;
-                if (P.gate) g = P.gate[(size_t)(P.row_req ? P.row_req[m] : 0) * P.gate_stride + n];
-                ((float*)P.out)[o] += g * v;
-              }
-            }
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          *(float*)(stg + (8 * (e >> 2) + 4 * half + (e & 3)) * RS + (j * 32 + (lane & 31)) * 4) = acc[i][j][e];
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+      for (int it = 0; it < 32 / RPI; ++it) {
+        const int row = it * RPI + lr;
+        const int m = m0 + wm * (BM / WM) + i * 32 + row;
+        float v[VEC];
+#pragma unroll
+        for (int c4 = 0; c4 < VEC / 4; ++c4) {
+          const f32x4 t4 = *(const f32x4*)(stg + row * RS + (lc + 4 * c4) * 4);
+#pragma unroll
+          for (int c = 0; c < 4; ++c) v[4 * c4 + c] = t4[c] + bv[4 * c4 + c];
+        }
+        if (m >= P.M || n >= P.N) continue;
+        const size_t o = (size_t)m * P.ldc + n;
+        if constexpr (KIND == OUT_RESID_F32) {
+          const float* gp = P.gate ? P.gate + (size_t)(P.row_req ? P.row_req[m] : 0) * P.gate_stride + n : nullptr;
+          float* xp = (float*)P.out + o;
+          if (full) {
+            f32x4 x4 = *(const f32x4*)xp;
+            f32x4 g4 = {1.f, 1.f, 1.f, 1.f};
+            if (gp) g4 = *(const f32x4*)gp;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) x4[c] += g4[c] * v[c];
+            *(f32x4*)xp = x4;
+          } else {
+            for (int c = 0; c < VEC && n + c < P.N; ++c) xp[c] += (gp ? gp[c] : 1.f) * v[c];
+          }
+        } else if constexpr (KIND == OUT_F32) {
+          float* xp = (float*)P.out + o;
+          if (full) {
+            f32x4 x4 = {v[0], v[1], v[2], v[3]};
+            *(f32x4*)xp = x4;
+          } else {
+            for (int c = 0; c < VEC && n + c < P.N; ++c) xp[c] = v[c];
+          }
+        } else {
+          if constexpr (KIND == OUT_GELU_BF16) {
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) v[c] = gelu_tanh(v[c]);
+          }
+          bf16_t* xp = (bf16_t*)P.out + o;
+          if (full) {
+            u32x4 w;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) w[c] = pack2bf(v[2 * c], v[2 * c + 1]);
+            *(u32x4*)xp = w;
+          } else {
+            for (int c = 0; c < VEC && n + c < P.N; ++c) xp[c] = f2bf(v[c]);
           }
         }
       }
+      asm volatile("" ::: "memory");
     }
   };
   if (P.out_kind == OUT_BF16) epilogue(std::integral_constant<int, OUT_BF16>{});
@@ -314,6 +418,15 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     case 21256256: launch_t<256, 256, 2, 4, 32, 5>(s, b); break;
     case 6256256: launch_t<256, 256, 2, 4, 64, 2, 2>(s, b); break;
     case 7256256: launch_t<256, 256, 2, 4, 64, 2, 3>(s, b); break;
+    case 8256256: launch_t<256, 256, 2, 4, 64, 2, 4>(s, b); break;
+    case 9256256: launch_t<256, 256, 2, 4, 64, 2, 5>(s, b); break;
+    case 12256256: launch_t<256, 256, 2, 4, 64, 2, 6>(s, b); break;
+    case 13256256: launch_t<256, 256, 2, 4, 32, 4, 2>(s, b); break;
+    case 14256256: launch_t<256, 256, 2, 4, 32, 5, 2>(s, b); break;
+    case 15256256: launch_t<256, 256, 2, 4, 32, 4, 3>(s, b); break;
+    case 16256256: launch_t<256, 256, 2, 4, 64, 2, 7>(s, b); break;
+    case 17256256: launch_t<256, 256, 2, 2, 64, 2, 3>(s, b); break;
+    case 18256256: launch_t<256, 256, 2, 2, 64, 2, 7>(s, b); break;
     case 256128: launch_t<256, 128, 2, 2, 64, 2>(s, b); break;
     case 128256: launch_t<128, 256, 2, 2, 64, 2>(s, b); break;
     case 10128128: launch_t<128, 128, 2, 2, 32, 4>(s, b); break;
