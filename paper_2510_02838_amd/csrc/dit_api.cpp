@@ -453,8 +453,7 @@ dit_status joint_block(dit_ctx* c, const Run& R, const std::string& p, const flo
   const float* mi = mod + mod_off + 6 * d;   // image stream: 6d
   {
     Scope sc(c, DIT_PROF_LNMOD, 0, 6.0 * Ns * d);
-    launch_ln_modulate(c->stream, x, h, Nt, d, mt, mt + d, MC, rreq, nullptr, nullptr);
-    launch_ln_modulate(c->stream, x + (size_t)Nt * d, h + (size_t)Nt * d, Ni, d, mi, mi + d, MC, rreq + Nt, nullptr, nullptr);
+    launch_ln_modulate(c->stream, x, h, Ns, d, mt, mt + d, MC, rreq, nullptr, nullptr, nullptr, Nt, mi, mi + d);
   }
   TAP(pt + ".ln1", h, Nt, d, 2, d); TAP(pi + ".ln1", h + (size_t)Nt * d, Ni, d, 2, d);
   run_gemm(c, {mk(h, d, Wm(c, pt + ".qkv.w"), Wld(c, pt + ".qkv.w"), Wv(c, pt + ".qkv.b"), Nt, 3 * d, d, OUT_BF16, qkv, 3 * d),
@@ -462,8 +461,8 @@ dit_status joint_block(dit_ctx* c, const Run& R, const std::string& p, const flo
   TAP(pt + ".qkv", qkv, Nt, 3 * d, 2, 3 * d); TAP(pi + ".qkv", qkv + (size_t)Nt * 3 * d, Ni, 3 * d, 2, 3 * d);
   {
     Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Ns * d);
-    launch_qknorm_rope(c->stream, qkv, 3 * d, Nt, g.n_heads, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, d, 1);
-    launch_qknorm_rope(c->stream, qkv + (size_t)Nt * 3 * d, 3 * d, Ni, g.n_heads, g.head_dim, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"), rope, s2j + Nt, q, k, d, d, 1);
+    launch_qknorm_rope(c->stream, qkv, 3 * d, Ns, g.n_heads, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, d, 1,
+                       Nt, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"));
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col), P.Nv_pad, vt, P.Nv_pad);
   }
   TAP(p + ".q", q, P.Nj, d, 2, d); TAP(p + ".k", k, P.Nj, d, 2, d);
@@ -475,8 +474,7 @@ dit_status joint_block(dit_ctx* c, const Run& R, const std::string& p, const flo
   TAP(pt + ".x_attn", x, Nt, d, 4, d); TAP(pi + ".x_attn", x + (size_t)Nt * d, Ni, d, 4, d);
   {
     Scope sc(c, DIT_PROF_LNMOD, 0, 6.0 * Ns * d);
-    launch_ln_modulate(c->stream, x, h, Nt, d, mt + 3 * d, mt + 4 * d, MC, rreq, nullptr, nullptr);
-    launch_ln_modulate(c->stream, x + (size_t)Nt * d, h + (size_t)Nt * d, Ni, d, mi + 3 * d, mi + 4 * d, MC, rreq + Nt, nullptr, nullptr);
+    launch_ln_modulate(c->stream, x, h, Ns, d, mt + 3 * d, mt + 4 * d, MC, rreq, nullptr, nullptr, nullptr, Nt, mi + 3 * d, mi + 4 * d);
   }
   run_gemm(c, {mk(h, d, Wm(c, pt + ".mlp1.w"), Wld(c, pt + ".mlp1.w"), Wv(c, pt + ".mlp1.b"), Nt, dff, d, OUT_GELU_BF16, act, dff),
                mk(h + (size_t)Nt * d, d, Wm(c, pi + ".mlp1.w"), Wld(c, pi + ".mlp1.w"), Wv(c, pi + ".mlp1.b"), Ni, dff, d, OUT_GELU_BF16, act + (size_t)Nt * dff, dff)});

@@ -47,7 +47,9 @@ void launch_attention(hipStream_t s, const AttnArgs& a);
 void launch_ln_modulate(hipStream_t s, const float* x, bf16_t* y, int M, int d,
                         const float* shift, const float* scale, int mod_stride,
                         const int* row_req, const float* gain, const float* beta,
-                        bf16_t* y_lo = nullptr);   // y_lo: optional second bf16 term (value - y)
+                        bf16_t* y_lo = nullptr,    // optional second bf16 term (value - y)
+                        int split = -1, const float* shift2 = nullptr, const float* scale2 = nullptr);
+                        // rows >= split use shift2/scale2 (two streams in one launch)
 
 // q/k per-head RMS norm (+ rotary) from a [M][ld] bf16 matrix holding q at column 0, k at
 // column d; writes rows to qo/ko at row dst_row[m] (or m).  rope: [n_dst_rows][dh/2] (cos,sin)
@@ -55,7 +57,8 @@ void launch_ln_modulate(hipStream_t s, const float* x, bf16_t* y, int M, int d,
 void launch_qknorm_rope(hipStream_t s, const bf16_t* qkv, int ld, int M, int H, int dh,
                         const float* qgain, const float* kgain, const float2* rope,
                         const int* dst_row, bf16_t* qo, bf16_t* ko, int ldo, int k_col_off,
-                        int do_k);
+                        int do_k, int split = -1, const float* qgain2 = nullptr,
+                        const float* kgain2 = nullptr);   // rows >= split use the second gains
 
 // V transpose: v rows [M][ld] at column v_col_off (+h*dh) -> vt[h][c][col], col = vt_col[m].
 // Tiles of 64 destination columns; tile t covers columns 64t..64t+63 and takes source

@@ -31,7 +31,9 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
                                                           const int* __restrict__ row_req,
                                                           const float* __restrict__ gain,
                                                           const float* __restrict__ beta,
-                                                          bf16_t* __restrict__ y_lo) {
+                                                          bf16_t* __restrict__ y_lo, int split,
+                                                          const float* __restrict__ shift2,
+                                                          const float* __restrict__ scale2) {
   const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
   if (row >= M) return;
   const int lane = threadIdx.x & 63;
@@ -60,7 +62,9 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
     sc = (const float4*)gain; sh = (const float4*)beta; plus_one = false;
   } else {
     const size_t mo = (size_t)(row_req ? row_req[row] : 0) * mod_stride;
-    sc = (const float4*)(scale + mo); sh = (const float4*)(shift + mo); plus_one = true;
+    const bool second = row >= split;     // rows from `split` on take the second stream's vectors
+    sc = (const float4*)((second ? scale2 : scale) + mo); sh = (const float4*)((second ? shift2 : shift) + mo);
+    plus_one = true;
   }
   uint2* yr = (uint2*)(y + (size_t)row * d);
 #pragma unroll
@@ -85,12 +89,13 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
 
 void launch_ln_modulate(hipStream_t s, const float* x, bf16_t* y, int M, int d, const float* shift,
                         const float* scale, int mod_stride, const int* row_req, const float* gain,
-                        const float* beta, bf16_t* y_lo) {
+                        const float* beta, bf16_t* y_lo, int split, const float* shift2, const float* scale2) {
+  if (split < 0 || !shift2) { split = M; shift2 = shift; scale2 = scale; }
   if (M == 0) return;
   dim3 g((M + 3) / 4), b(256);
-  if (d <= 1024) hipLaunchKernelGGL(ln_modulate_kernel<4>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo);
-  else if (d <= 3072) hipLaunchKernelGGL(ln_modulate_kernel<12>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo);
-  else hipLaunchKernelGGL(ln_modulate_kernel<20>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo);
+  if (d <= 1024) hipLaunchKernelGGL(ln_modulate_kernel<4>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo, split, shift2, scale2);
+  else if (d <= 3072) hipLaunchKernelGGL(ln_modulate_kernel<12>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo, split, shift2, scale2);
+  else hipLaunchKernelGGL(ln_modulate_kernel<20>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo, split, shift2, scale2);
 }
 
 // ---------------------------------------------------------------------------------------
@@ -104,8 +109,11 @@ __global__ __launch_bounds__(256) void qknorm_rope_kernel(const bf16_t* __restri
                                                           const float2* __restrict__ rope,
                                                           const int* __restrict__ dst_row,
                                                           bf16_t* __restrict__ qo, bf16_t* __restrict__ ko,
-                                                          int ldo, int k_col_off, int do_k) {
+                                                          int ldo, int k_col_off, int do_k, int split,
+                                                          const float* __restrict__ qgain2,
+                                                          const float* __restrict__ kgain2) {
   const int row = blockIdx.x;
+  if (row >= split) { qgain = qgain2; kgain = kgain2; }   // second stream's gains
   const int pair = blockIdx.y * 256 + threadIdx.x;     // pair index within the row's d/2 pairs
   const bool ok = pair < (d >> 1);
   const int col = ok ? pair * 2 : 0;
@@ -133,12 +141,13 @@ __global__ __launch_bounds__(256) void qknorm_rope_kernel(const bf16_t* __restri
 
 void launch_qknorm_rope(hipStream_t s, const bf16_t* qkv, int ld, int M, int H, int dh, const float* qgain,
                         const float* kgain, const float2* rope, const int* dst_row, bf16_t* qo, bf16_t* ko,
-                        int ldo, int k_col_off, int do_k) {
+                        int ldo, int k_col_off, int do_k, int split, const float* qgain2, const float* kgain2) {
   if (M == 0) return;
+  if (split < 0 || !qgain2) { split = M; qgain2 = qgain; kgain2 = kgain; }
   const int d = H * dh;
   dim3 g(M, (d / 2 + 255) / 256), b(256);
-  if (dh == 64) hipLaunchKernelGGL(qknorm_rope_kernel<64>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k);
-  else hipLaunchKernelGGL(qknorm_rope_kernel<128>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k);
+  if (dh == 64) hipLaunchKernelGGL(qknorm_rope_kernel<64>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k, split, qgain2, kgain2);
+  else hipLaunchKernelGGL(qknorm_rope_kernel<128>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k, split, qgain2, kgain2);
 }
 
 // ---------------------------------------------------------------------------------------
