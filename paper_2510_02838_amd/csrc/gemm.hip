@@ -56,9 +56,11 @@ __device__ __forceinline__ uint32_t pack2bf(float a, float b) {
 }
 
 __device__ __forceinline__ float gelu_tanh(float x) {
-  // 0.5 x (1 + tanh(u)) == x * sigmoid(2u),  u = sqrt(2/pi) (x + 0.044715 x^3)
-  float u = 0.7978845608028654f * (x + 0.044715f * x * x * x);
-  return x / (1.0f + __expf(-2.0f * u));
+  // 0.5 x (1 + tanh(u)) == x * sigmoid(2u) == x / (1 + 2^(-2 log2(e) u)),
+  // u = sqrt(2/pi) (x + 0.044715 x^3); hardware exp2 and reciprocal (1 ulp each)
+  const float t = x * (0.7978845608028654f + 0.035677408136300125f * x * x);
+  const float e = __builtin_amdgcn_exp2f(-2.8853900817779268f * t);
+  return x * __builtin_amdgcn_rcpf(1.0f + e);
 }
 
 template <int BKT>
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 
   // ---- workgroup -> (problem, tile) ----------------------------------------------------
   int bid = blockIdx.x, nb = gridDim.x;
-  if (MODE != 5) {
+  {
     int x = bid & 7, idx = bid >> 3, q = nb >> 3, rem = nb & 7;
     bid = x * q + (x < rem ? x : rem) + idx;
   }
@@ -194,50 +196,6 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
   };
 
-  if constexpr (MODE == 4) {
-    // probe: the same global reads into registers (no LDS), two slabs in flight
-    u32x4 r0[LPS], r1[LPS], sink = {0, 0, 0, 0};
-    auto rd = [&](int kt, u32x4 (&r)[LPS]) {
-      const int ks = (kt < nk ? kt : nk - 1) * BKT;
-#pragma unroll
-      for (int i = 0; i < LA; ++i) r[i] = *(const u32x4*)(P.A + ks + ga[i]);
-#pragma unroll
-      for (int i = 0; i < LB; ++i) r[LA + i] = *(const u32x4*)(P.W + ks + gb[i]);
-    };
-    rd(0, r0);
-    for (int kt = 0; kt < nk; kt += 2) {
-      rd(kt + 1, r1);
-#pragma unroll
-      for (int i = 0; i < LPS; ++i) sink ^= r0[i];
-      rd(kt + 2, r0);
-#pragma unroll
-      for (int i = 0; i < LPS; ++i) sink ^= r1[i];
-    }
-    acc[0][0][0] = __uint_as_float(sink[0] ^ sink[1] ^ sink[2] ^ sink[3]);
-  } else if constexpr (MODE == 6) {
-    // probe: global -> registers -> ds_write_b128 into the ring, one slab in flight, one barrier
-    // per slab (the traffic pattern of MODE 2 without the LDS-DMA path)
-    u32x4 r[LPS];
-    auto rd = [&](int kt) {
-      const int ks = (kt < nk ? kt : nk - 1) * BKT;
-#pragma unroll
-      for (int i = 0; i < LA; ++i) r[i] = *(const u32x4*)(P.A + ks + ga[i]);
-#pragma unroll
-      for (int i = 0; i < LB; ++i) r[LA + i] = *(const u32x4*)(P.W + ks + gb[i]);
-    };
-    rd(0);
-    for (int kt = 0; kt < nk; ++kt) {
-      unsigned char* dA = smem + (kt % NS) * STAGE;
-#pragma unroll
-      for (int i = 0; i < LA; ++i) *(u32x4*)(dA + (i * NT + tid) * 16) = r[i];
-#pragma unroll
-      for (int i = 0; i < LB; ++i) *(u32x4*)(dA + OFFB + (i * NT + tid) * 16) = r[LA + i];
-      __syncthreads();
-      rd(kt + 1);
-    }
-    bf16x8 a1[TM], b1[TN];
-    load_frags(smem, 1, a1, b1); mfma_all(a1, b1);
-  } else {
   bf16x8 a0[TM], b0[TN], a1[TM], b1[TN];
 #pragma unroll
   for (int sidx = 0; sidx < NS; ++sidx) issue(sidx);
@@ -249,7 +207,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     const unsigned char* cur = smem + st_cur * STAGE;
     const int st_nxt = st_cur + 1 == NS ? 0 : st_cur + 1;
     const unsigned char* nxt = smem + st_nxt * STAGE;
-    if (MODE != 2 && MODE != 5) {
+    if (MODE != 2) {
       load_frags(cur, 1, a1, b1);
       mfma_all(a0, b0);
       interleave_hint<TM + TN, TM * TN>();
@@ -265,10 +223,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     // The last fragments of this slab are on their way to registers; slabs kt+1..kt+NS-1 are in
     // flight.  Wait for slab kt+1 (mine) and my fragments; after the barrier nobody reads `cur`
     // any more and `nxt` is visible to all.
-    if (MODE == 3 || MODE == 7) wait_vm<63, true>(); else wait_vm<(NS - 2) * LPS, true>();
-    if (MODE != 7) __syncthreads();
-    if (MODE != 3 && MODE != 7) issue(kt + NS);           // into the stage of slab kt
-    if (MODE != 2 && MODE != 5) {
+    if (MODE == 3) wait_vm<63, true>(); else wait_vm<(NS - 2) * LPS, true>();
+    __syncthreads();
+    if (MODE != 3) issue(kt + NS);           // into the stage of slab kt
+    if (MODE != 2) {
       load_frags(nxt, 0, a0, b0);            // (after the last slab this reads a stale stage; unused)
       mfma_all(a1, b1);
       interleave_hint<TM + TN, TM * TN>();
@@ -276,8 +234,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     st_cur = st_nxt;
   }
   wait_vm<0, true>();                        // drain the redundant tail loads before LDS is released
-  if (MODE == 2 || MODE == 5) { load_frags(smem, 1, a1, b1); mfma_all(a1, b1); }
-  }
+  if (MODE == 2) { load_frags(smem, 1, a1, b1); mfma_all(a1, b1); }
 
   // ---- epilogue ---------------------------------------------------------------------------
   // acc[i][j][e] is C[32i + 8*(e/4) + 4*half + e%4][32j + lane%32] of the wave's sub-tile: a lane
@@ -418,15 +375,6 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     case 21256256: launch_t<256, 256, 2, 4, 32, 5>(s, b); break;
     case 6256256: launch_t<256, 256, 2, 4, 64, 2, 2>(s, b); break;
     case 7256256: launch_t<256, 256, 2, 4, 64, 2, 3>(s, b); break;
-    case 8256256: launch_t<256, 256, 2, 4, 64, 2, 4>(s, b); break;
-    case 9256256: launch_t<256, 256, 2, 4, 64, 2, 5>(s, b); break;
-    case 12256256: launch_t<256, 256, 2, 4, 64, 2, 6>(s, b); break;
-    case 13256256: launch_t<256, 256, 2, 4, 32, 4, 2>(s, b); break;
-    case 14256256: launch_t<256, 256, 2, 4, 32, 5, 2>(s, b); break;
-    case 15256256: launch_t<256, 256, 2, 4, 32, 4, 3>(s, b); break;
-    case 16256256: launch_t<256, 256, 2, 4, 64, 2, 7>(s, b); break;
-    case 17256256: launch_t<256, 256, 2, 2, 64, 2, 3>(s, b); break;
-    case 18256256: launch_t<256, 256, 2, 2, 64, 2, 7>(s, b); break;
     case 256128: launch_t<256, 128, 2, 2, 64, 2>(s, b); break;
     case 128256: launch_t<128, 256, 2, 2, 64, 2>(s, b); break;
     case 10128128: launch_t<128, 128, 2, 2, 32, 4>(s, b); break;

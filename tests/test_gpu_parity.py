@@ -398,3 +398,45 @@ def test_wan_full_width_32760_tokens_one_block_sampled_rows(torch):
     rms = float(np.sqrt((want * want).mean()))
     assert rms > 1.0
     assert max_abs(g, want) <= STEP_MAX_ABS * rms, (max_abs(g, want), rms)
+
+
+# ----------------------------------------------------------------------- error behaviour
+def test_failing_calls_leave_buffers_untouched(torch, B):
+    """Errors are detected before anything is launched: status code, message, buffers intact."""
+    cfg = synth.CONFIGS["tiny"]
+    case = Case(torch, cfg["arch"], synth.make_requests("tiny"), cfg["steps"])
+    x = case.dev_latents()
+    before = x.clone()
+    reqs = B.make_reqs(case.reqs)
+    fp = lambda a: a.ctypes.data_as(C.POINTER(C.c_float))
+    one, half = np.array([1.0], np.float32), np.array([0.5], np.float32)
+    # DDIM from sigma = 1 is undefined
+    st = B.dit_denoise_step(case.m.ctx, 1, reqs, x.data_ptr(), case.d_cond.data_ptr(), fp(one), fp(half), 1, None)
+    assert st == 1 and b"DDIM" in B.dit_last_error(case.m.ctx)
+    # unknown update kind, non-finite sigma, latent not divisible by the patch, too many steps
+    assert B.dit_denoise_step(case.m.ctx, 1, reqs, x.data_ptr(), case.d_cond.data_ptr(), fp(half), fp(half), 7, None) == 1
+    nan = np.array([np.nan], np.float32)
+    assert B.dit_denoise_step(case.m.ctx, 1, reqs, x.data_ptr(), case.d_cond.data_ptr(), fp(nan), fp(half), 0, None) == 1
+    bad = B.make_reqs([(1, 15, 16, 16)])
+    assert B.dit_denoise_step(case.m.ctx, 1, bad, x.data_ptr(), case.d_cond.data_ptr(), fp(half), fp(half), 0, None) == 2
+    many = np.ascontiguousarray(np.linspace(1, 0, 201, dtype=np.float32)[None])
+    st = B.dit_sample(case.m.ctx, 1, reqs, x.data_ptr(), case.d_cond.data_ptr(), fp(many), 200, 0)
+    assert st == 3 and b"workspace" in B.dit_last_error(case.m.ctx)
+    # a larger batch than the workspace was sized for
+    big = B.make_reqs([(1, 64, 64, 16)] * 4)
+    assert B.dit_denoise_step(case.m.ctx, 4, big, x.data_ptr(), case.d_cond.data_ptr(), fp(np.ones(4, np.float32) * .5),
+                              fp(np.ones(4, np.float32) * .4), 0, None) == 3
+    torch.cuda.synchronize()
+    assert torch.equal(x, before)
+    # unknown tensor / tap names
+    assert B.dit_get_tensor(case.m.ctx, b"no.such.tensor", fp(np.zeros(4, np.float32)), 4) == 6
+    assert B.dit_tap_info(case.m.ctx, b"nothing", None, None, None) == 6
+    # and the context still works afterwards
+    check_step(case, 0)
+
+
+def test_single_token_condition_and_smallest_latent(torch):
+    """Degenerate sizes: one condition token, a 2x2 latent (one image token), batch of 3."""
+    arch = synth.CONFIGS["tiny"]["arch"]
+    case = Case(torch, arch, [(1, 2, 2, 1), (1, 2, 4, 1), (1, 4, 2, 3)], 2, std=0.06, bias_std=0.1)
+    check_step(case, 0)
