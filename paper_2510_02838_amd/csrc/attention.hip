@@ -187,11 +187,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
   __syncthreads();
   if (n_kt > 1) issue_k(1);
   issue_v(0);
-  f32x16 sc[2], sn[2];
+  f32x16 sc[2], sn[2];     // score tiles of the current and the next key tile
   scores(0, sc);
   float mx = row_max(sc);
 
-  for (int kt = 0; kt < n_kt; ++kt) {
+  // One iteration; `sc` holds S(kt) on entry, `sn` receives S(kt+1).  The loop below calls it
+  // with the two register sets swapped on alternate tiles instead of copying sn to sc.
+  auto step = [&](int kt, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
     // ---- (A) raise the running max only when a row's tile max exceeds it by more than 2^8
     // in the exponent (softmax is shift-invariant, so a stale max is exact as long as nothing
     // overflows: probabilities stay below 2^8); this skips the rescale of O on most tiles.
@@ -259,8 +261,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
         }
       l_run -= corr;
     }
-#pragma unroll
-    for (int t = 0; t < 2; ++t) sc[t] = sn[t];
+  };
+  for (int kt = 0; kt < n_kt; kt += 2) {
+    step(kt, sc, sn);
+    if (kt + 1 < n_kt) step(kt + 1, sn, sc);
   }
 
   // ---- normalise and store -------------------------------------------------------------------
