@@ -19,9 +19,13 @@
 using namespace dit;
 
 namespace dit {
-int attn_q_per_tile() {
-  static const int v = [] { const char* e = getenv("DIT_ATTN_QB"); return e && atoi(e) == 256 ? 256 : 128; }();
-  return v;
+// Queries per attention workgroup.  256 (8 waves) halves the K/V traffic into LDS per query and
+// measured 5% faster at 32760 tokens with head_dim 128; 128 (4 waves) gives twice as many
+// workgroups, which wins on short sequences.  DIT_ATTN_QB=128|256 overrides.
+int attn_q_per_tile(int longest_segment, int head_dim) {
+  static const int forced = [] { const char* e = getenv("DIT_ATTN_QB"); return e ? atoi(e) : 0; }();
+  if (forced == 128 || forced == 256) return forced;
+  return (head_dim == 128 && longest_segment >= 16384) ? 256 : 128;
 }
 }  // namespace dit
 
@@ -46,6 +50,7 @@ struct Plan {
   bool has_txt_stream = false;          // J, F: text tokens carry a residual stream
   int Nt = 0, Ni = 0, Ns = 0, Nj = 0;   // text rows, image rows, stream rows, joint rows
   int Nv_pad = 0, Nvx_pad = 0;          // V^T columns (self, cross)
+  int qb = 128;                         // queries per attention workgroup
   long long lat_total = 0;
   std::vector<int> cu_txt, cu_img, cu_joint, vt_off, vtx_off;
   std::vector<long long> lat_off;
@@ -60,7 +65,7 @@ struct Plan {
 };
 
 struct WsLayout {
-  size_t meta, sig, coef_a, coef_b, feat, th1, vec, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, o, act, cproj,
+  size_t meta, sig, coef_a, coef_b, feat, th1, vec, mhi, mlo, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, o, act, cproj,
       patch, yfin, rope, total;
   int MC = 0;        // modulation columns per conditioning row
   int R = 0;         // conditioning rows = steps * n_req
@@ -270,6 +275,9 @@ void build_plan(const dit_ctx* c, int n_req, const dit_req* reqs, Plan& P) {
   std::vector<int> row_req_s(P.Ns), row_req_j(P.Nj), s2j(P.Ns), j2s(P.Nj), tok_of_row(P.Nj, -1);
   std::vector<int> src_of_col(P.Nv_pad, -1), src_of_col_j(P.Nv_pad, -1), src_of_col_x(P.Nvx_pad, -1);
   std::vector<int> txt_rows(std::max(P.Nt, 1));
+  int longest = 0;
+  for (int r = 0; r < n_req; ++r) longest = std::max(longest, P.cu_joint[r + 1] - P.cu_joint[r]);
+  P.qb = attn_q_per_tile(longest, g.head_dim);
   for (int r = 0; r < n_req; ++r) {
     const int nt = P.cu_txt[r + 1] - P.cu_txt[r], ni = P.cu_img[r + 1] - P.cu_img[r];
     int j = P.cu_joint[r];
@@ -289,8 +297,8 @@ void build_plan(const dit_ctx* c, int n_req, const dit_req* reqs, Plan& P) {
       src_of_col_j[P.vt_off[r] + t] = P.cu_joint[r] + t;
     }
     for (int t = 0; t < nt; ++t) src_of_col_x[P.vtx_off[r] + t] = P.cu_txt[r] + t;
-    for (int q0 = 0; q0 < nj; q0 += attn_q_per_tile()) P.tiles.push_back(AttnTile{r, q0});
-    for (int q0 = 0; q0 < ni; q0 += attn_q_per_tile()) P.xtiles.push_back(AttnTile{r, q0});
+    for (int q0 = 0; q0 < nj; q0 += P.qb) P.tiles.push_back(AttnTile{r, q0});
+    for (int q0 = 0; q0 < ni; q0 += P.qb) P.xtiles.push_back(AttnTile{r, q0});
   }
   // longest key ranges first, so that the tail of the grid is made of short tiles
   std::stable_sort(P.tiles.begin(), P.tiles.end(), [&](const AttnTile& a, const AttnTile& b) {
@@ -335,6 +343,8 @@ void layout_ws(const dit_ctx* c, const Plan& P, int max_steps, WsLayout& L) {
   L.feat = take((size_t)L.R * T_FREQ * 4);
   L.th1 = take((size_t)L.R * d * 4);
   L.vec = take((size_t)L.R * d * 4);
+  L.mhi = take((size_t)L.R * d * 2);
+  L.mlo = take((size_t)L.R * d * 2);
   L.mod = take((size_t)L.R * L.MC * 4);
   L.modblk = take((size_t)P.n_req * 6 * d * 4);
   L.x = take(Ns * d * 4);
@@ -358,7 +368,7 @@ void layout_ws(const dit_ctx* c, const Plan& P, int max_steps, WsLayout& L) {
 // launch helpers with profiling
 // ---------------------------------------------------------------------------------------
 struct Scope {
-  dit_ctx* c; int klass; bool on;
+  dit_ctx* c; int klass; bool on; hipEvent_t end = nullptr;
   Scope(dit_ctx* c_, int k, double flop, double bytes) : c(c_), klass(k), on(c_->prof) {
     if (!on) return;
     c->prof_flop[k] += flop; c->prof_bytes[k] += bytes;
@@ -366,9 +376,10 @@ struct Scope {
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) { on = false; return; }
     c->ev_pool.push_back(e0); c->ev_pool.push_back(e1);
     c->ev_recs.push_back({k});
+    end = e1;
     (void)hipEventRecord(e0, c->stream);
   }
-  ~Scope() { if (on) (void)hipEventRecord(c->ev_pool.back(), c->stream); }
+  ~Scope() { if (on) (void)hipEventRecord(end, c->stream); }   // (scopes may nest)
 };
 
 GemmProblem mk(const bf16_t* A, int lda, const bf16_t* W, int ldw, const float* bias, int M, int N, int K,
@@ -430,7 +441,7 @@ void run_attention(dit_ctx* c, const Run& R, const bf16_t* q, int ldq, const bf1
   AttnArgs a;
   a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.ldvt = ldvt; a.o = o; a.ldo = ldo;
   a.n_heads = g.n_heads; a.head_dim = g.head_dim; a.cu_q = cu_q; a.cu_k = cu_k; a.vt_off = vt_off;
-  a.tiles = tiles; a.n_tiles = n_tiles; a.o_row_map = o_row_map; a.q_per_tile = attn_q_per_tile();
+  a.tiles = tiles; a.n_tiles = n_tiles; a.o_row_map = o_row_map; a.q_per_tile = R.P.qb;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
   Scope sc(c, DIT_PROF_ATTN, flop_units * g.hidden, 0);
   launch_attention(c->stream, a);
@@ -648,8 +659,18 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
     launch_skinny(s, R.at<float>(L.th1), d, Wm(c, "t_embed.2.w"), Wld(c, "t_embed.2.w"), Wv(c, "t_embed.2.b"), R.at<float>(L.vec), d, Rr, d, d, 1);
     const float* vec = R.at<float>(L.vec);
     int off = 0;
+    // With many conditioning rows (steps x requests) the modulation products go to the MFMA
+    // GEMM: SiLU(vec) enters as two bf16 terms, so the result agrees with the fp32 path to
+    // ~1e-5 relative; with few rows the fp32 matrix-vector kernel is used.
+    const bool big = Rr >= 16;
+    if (big) launch_silu_split(s, vec, R.at<bf16_t>(L.mhi), R.at<bf16_t>(L.mlo), (long long)Rr * d);
     auto modv = [&](const std::string& name, int n) {
-      launch_skinny(s, vec, d, Wm(c, name + ".w"), Wld(c, name + ".w"), Wv(c, name + ".b"), mod + off, MC, Rr, n, d, 1);
+      if (big) {
+        run_gemm(c, {mk(R.at<bf16_t>(L.mhi), d, Wm(c, name + ".w"), Wld(c, name + ".w"), Wv(c, name + ".b"), Rr, n, d, OUT_F32, mod + off, MC)});
+        run_gemm(c, {mk(R.at<bf16_t>(L.mlo), d, Wm(c, name + ".w"), Wld(c, name + ".w"), nullptr, Rr, n, d, OUT_RESID_F32, mod + off, MC)});
+      } else {
+        launch_skinny(s, vec, d, Wm(c, name + ".w"), Wld(c, name + ".w"), Wv(c, name + ".b"), mod + off, MC, Rr, n, d, 1);
+      }
       off += n;
     };
     if (g.family == DIT_FAMILY_W) modv("t_proj", 6 * d);
@@ -999,11 +1020,14 @@ dit_status dit_op_attention(void* stream, const void* q, int ldq, const void* k,
   const int d = n_heads * head_dim;
   if (ldq < d || ldk < d || ldo < d || ldq % 8 || ldk % 8 || ldo % 4 || ldvt % 64) return DIT_ESHAPE;
   std::vector<AttnTile> tiles;
+  int longest = 0;
+  for (int s = 0; s < n_seg; ++s) longest = std::max(longest, cu_k[s + 1] - cu_k[s]);
+  const int qb = attn_q_per_tile(longest, head_dim);
   for (int s = 0; s < n_seg; ++s) {
     const int nq = cu_q[s + 1] - cu_q[s], nk = cu_k[s + 1] - cu_k[s];
     if (nq < 0 || nk <= 0 || vt_off[s] % 64 || vt_off[s] < 0) return DIT_ESHAPE;
     if (vt_off[s] + (int)rup(nk, 64) > ldvt) return DIT_ESHAPE;
-    for (int q0 = 0; q0 < nq; q0 += attn_q_per_tile()) tiles.push_back(AttnTile{s, q0});
+    for (int q0 = 0; q0 < nq; q0 += qb) tiles.push_back(AttnTile{s, q0});
   }
   if (work_bytes < dit_op_attention_work_bytes(n_seg, cu_q)) return DIT_ENOMEM;
   std::stable_sort(tiles.begin(), tiles.end(), [&](const AttnTile& a, const AttnTile& b) {
@@ -1023,7 +1047,7 @@ dit_status dit_op_attention(void* stream, const void* q, int ldq, const void* k,
   a.o = (bf16_t*)o; a.ldo = ldo; a.n_heads = n_heads; a.head_dim = head_dim;
   a.cu_q = (const int*)w; a.cu_k = (const int*)(w + cu_b); a.vt_off = (const int*)(w + 2 * cu_b);
   a.tiles = (const AttnTile*)(w + 2 * cu_b + vo_b); a.n_tiles = (int)tiles.size(); a.o_row_map = nullptr;
-  a.q_per_tile = attn_q_per_tile();
+  a.q_per_tile = qb;
   a.scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
   launch_attention(s, a);
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;

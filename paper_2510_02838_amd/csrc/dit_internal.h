@@ -27,7 +27,7 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile = 0);
 
 // ---- attention ----------------------------------------------------------------------
 struct AttnTile { int seg; int q0; };   // one block of q_per_tile queries of one segment
-int attn_q_per_tile();                  // 128 or 256: queries per workgroup (tuning knob)
+int attn_q_per_tile(int longest_segment, int head_dim);   // 128 or 256 queries per workgroup
 struct AttnArgs {
   const bf16_t* q; int ldq;
   const bf16_t* k; int ldk;
@@ -74,6 +74,7 @@ void launch_skinny(hipStream_t s, const float* x, int ldx, const bf16_t* W, int 
                    const float* bias, float* y, int ldy, int M, int N, int K, int silu_in);
 
 void launch_timestep_features(hipStream_t s, const float* sigma_dev, float* out, int M);
+void launch_silu_split(hipStream_t s, const float* x, bf16_t* hi, bf16_t* lo, long long n);
 
 // patchify: latents fp32 packed -> bf16 [n_img][ldp] (columns >= pdim zero)
 struct TokInfo { int req; int f, i, j; };  // per image token: request and grid position

@@ -99,8 +99,8 @@ void launch_ln_modulate(hipStream_t s, const float* x, bf16_t* y, int M, int d, 
 }
 
 // ---------------------------------------------------------------------------------------
-// q/k per-head RMS norm (+ rotary code).  A thread owns one adjacent pair (2j, 2j+1) of one
-// head of one row; the dh/2 threads of a head reduce with shuffles.
+// q/k per-head RMS norm (+ rotary code).  A lane owns 8 consecutive elements (16 bytes) of one
+// head of one row; the dh/8 lanes of a head reduce with shuffles.
 // ---------------------------------------------------------------------------------------
 template <int DH>
 __global__ __launch_bounds__(256) void qknorm_rope_kernel(const bf16_t* __restrict__ qkv, int ld, int M, int d,
@@ -112,30 +112,50 @@ __global__ __launch_bounds__(256) void qknorm_rope_kernel(const bf16_t* __restri
                                                           int ldo, int k_col_off, int do_k, int split,
                                                           const float* __restrict__ qgain2,
                                                           const float* __restrict__ kgain2) {
-  const int row = blockIdx.x;
+  const int cpr = d >> 3;                                // 16-byte chunks per row
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const bool ok = idx < (long long)M * cpr;              // (heads never straddle the tail: cpr % (DH/8) == 0)
+  const int row = ok ? (int)(idx / cpr) : M - 1;
+  const int col = ok ? (int)(idx % cpr) * 8 : 0;
   if (row >= split) { qgain = qgain2; kgain = kgain2; }   // second stream's gains
-  const int pair = blockIdx.y * 256 + threadIdx.x;     // pair index within the row's d/2 pairs
-  const bool ok = pair < (d >> 1);
-  const int col = ok ? pair * 2 : 0;
-  const int j = (col % DH) >> 1;                        // pair index within the head
+  const int hc = col % DH;                               // first element within the head
   const int drow = dst_row ? dst_row[row] : row;
-  float2 cs = make_float2(1.f, 0.f);
-  if (rope) cs = rope[(size_t)drow * (DH / 2) + j];
+  float2 cs[4];
+#pragma unroll
+  for (int p = 0; p < 4; ++p) cs[p] = make_float2(1.f, 0.f);
+  if (rope) {
+    const float4* rp = (const float4*)(rope + (size_t)drow * (DH / 2) + (hc >> 1));
+    const float4 r0 = rp[0], r1 = rp[1];
+    cs[0] = make_float2(r0.x, r0.y); cs[1] = make_float2(r0.z, r0.w);
+    cs[2] = make_float2(r1.x, r1.y); cs[3] = make_float2(r1.z, r1.w);
+  }
 #pragma unroll
   for (int which = 0; which < 2; ++which) {
     if (which == 1 && !do_k) break;
-    const bf16_t* src = qkv + (size_t)row * ld + (which ? k_col_off : 0) + col;
-    const uint32_t raw = *(const uint32_t*)src;
-    float x0 = bf2f((uint16_t)(raw & 0xFFFF)), x1 = bf2f((uint16_t)(raw >> 16));
-    float ss = x0 * x0 + x1 * x1;
+    const uint4 raw = *(const uint4*)(qkv + (size_t)row * ld + (which ? k_col_off : 0) + col);
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    float x[8];
+    float ss = 0.f;
 #pragma unroll
-    for (int o = DH / 4; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
+    for (int p = 0; p < 4; ++p) {
+      x[2 * p] = bf2f((uint16_t)(w[p] & 0xFFFF));
+      x[2 * p + 1] = bf2f((uint16_t)(w[p] >> 16));
+      ss += x[2 * p] * x[2 * p] + x[2 * p + 1] * x[2 * p + 1];
+    }
+#pragma unroll
+    for (int o = DH / 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
     const float r = rsqrtf(ss / (float)DH + 1e-6f);
-    const float* g = which ? kgain : qgain;
-    x0 = x0 * r * g[2 * j];
-    x1 = x1 * r * g[2 * j + 1];
-    const float y0 = x0 * cs.x - x1 * cs.y, y1 = x0 * cs.y + x1 * cs.x;
-    if (ok) *(uint32_t*)((which ? ko : qo) + (size_t)drow * ldo + col) = pack2(y0, y1);
+    const float4* gp = (const float4*)((which ? kgain : qgain) + hc);
+    const float4 g0 = gp[0], g1 = gp[1];
+    const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+    uint4 out;
+    uint32_t* ow = (uint32_t*)&out;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const float a = x[2 * p] * r * g[2 * p], b = x[2 * p + 1] * r * g[2 * p + 1];
+      ow[p] = pack2(a * cs[p].x - b * cs[p].y, a * cs[p].y + b * cs[p].x);
+    }
+    if (ok) *(uint4*)((which ? ko : qo) + (size_t)drow * ldo + col) = out;
   }
 }
 
@@ -145,7 +165,8 @@ void launch_qknorm_rope(hipStream_t s, const bf16_t* qkv, int ld, int M, int H, 
   if (M == 0) return;
   if (split < 0 || !qgain2) { split = M; qgain2 = qgain; kgain2 = kgain; }
   const int d = H * dh;
-  dim3 g(M, (d / 2 + 255) / 256), b(256);
+  const long long total = (long long)M * (d / 8);
+  dim3 g((unsigned)((total + 255) / 256)), b(256);
   if (dh == 64) hipLaunchKernelGGL(qknorm_rope_kernel<64>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k, split, qgain2, kgain2);
   else hipLaunchKernelGGL(qknorm_rope_kernel<128>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k, split, qgain2, kgain2);
 }
@@ -248,6 +269,21 @@ void launch_skinny(hipStream_t s, const float* x, int ldx, const bf16_t* W, int 
                    int ldy, int M, int N, int K, int silu_in) {
   if (M == 0 || N == 0) return;
   hipLaunchKernelGGL(skinny_kernel, dim3((N + 3) / 4), dim3(256), 0, s, x, ldx, W, ldw, bias, y, ldy, M, N, K, silu_in);
+}
+
+// hi + lo = SiLU(x) as two bf16 terms (about 16 mantissa bits), for feeding an MFMA GEMM
+__global__ __launch_bounds__(256) void silu_split_kernel(const float* __restrict__ x, bf16_t* __restrict__ hi,
+                                                         bf16_t* __restrict__ lo, long long n) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const float v = silu_f(x[i]);
+  const uint16_t h = f2bf(v);
+  hi[i] = h;
+  lo[i] = f2bf(v - bf2f(h));
+}
+void launch_silu_split(hipStream_t s, const float* x, bf16_t* hi, bf16_t* lo, long long n) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(silu_split_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, hi, lo, n);
 }
 
 // out[m][0..127] = cos(1000 sigma f_k), out[m][128..255] = sin(...), f_k = exp(-ln(1e4) k/128)
