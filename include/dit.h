@@ -173,10 +173,19 @@ dit_status dit_op_gemm(void* stream, const void* A, int lda, const void* W, int 
 /* As dit_op_gemm (out_kind 0..2 only) with the tile variant forced, for tuning sweeps:
  * BM*1000+BN in {256256, 256128, 128256, 128128}; +1000000 = 8 waves (256256 only);
  * +10000000 / +20000000 = k-slab 32 with a 4- / 5-stage LDS ring instead of k-slab 64 with
- * 2 stages (256256, 1256256, 128128). */
+ * 2 stages (256256, 1256256, 128128); 30128128 = 128x128 with k-slab 64 and a 4-stage ring. */
 dit_status dit_op_gemm_variant(void* stream, const void* A, int lda, const void* W, int ldw,
                                const float* bias, int M, int N, int K, int out_kind, void* out,
                                int ldc, int variant);
+
+/* As dit_op_gemm, computed as `splits` partial products over disjoint shares of K (each a
+ * whole number of 64-wide slabs, 1 <= splits <= K/64) that a second kernel sums in fixed
+ * order before the epilogue: the form the denoising step uses when M is small (few tiles,
+ * long K).  work: dev scratch of at least ceil(M/128)*ceil(N/128)*splits*65536 bytes. */
+dit_status dit_op_gemm_splitk(void* stream, const void* A, int lda, const void* W, int ldw,
+                              const float* bias, int M, int N, int K, int out_kind, void* out,
+                              int ldc, const float* gate, int gate_stride, const int* row_req,
+                              int splits, void* work, size_t work_bytes);
 
 /* Flash-style attention over packed segments: softmax(Q K^T / sqrt(dh)) V per segment and
  * head, no other mask.  q: dev bf16 rows [Nq][H*dh] with row stride ldq (elements); k likewise

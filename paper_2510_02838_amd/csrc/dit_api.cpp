@@ -66,7 +66,7 @@ struct Plan {
 
 struct WsLayout {
   size_t meta, sig, coef_a, coef_b, feat, th1, vec, mhi, mlo, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, o, act, cproj,
-      patch, yfin, rope, total;
+      patch, yfin, rope, partial, total;
   int MC = 0;        // modulation columns per conditioning row
   int R = 0;         // conditioning rows = steps * n_req
   int ldp = 0, ldy = 0;
@@ -99,6 +99,7 @@ struct dit_ctx {
   Slot slots[4];
   int next_slot = 0;
   int pdim = 0;
+  float* gemm_partial = nullptr;   // split-K scratch inside the workspace of the running call
 };
 
 namespace {
@@ -325,6 +326,9 @@ int mod_cols(const dit_config& g) {
   return 6 * d + 2 * d;
 }
 
+// split-K scratch: at most 256 workgroups, each leaving one 128x128 fp32 tile
+constexpr size_t GEMM_PARTIAL_BYTES = (size_t)256 * 128 * 128 * 4;
+
 void layout_ws(const dit_ctx* c, const Plan& P, int max_steps, WsLayout& L) {
   const dit_config& g = c->cfg;
   const size_t d = g.hidden, dff = g.mlp_hidden;
@@ -361,6 +365,7 @@ void layout_ws(const dit_ctx* c, const Plan& P, int max_steps, WsLayout& L) {
   L.patch = take(Ni * (size_t)L.ldp * 2 * 2);   // hi and lo terms
   L.yfin = take(Ni * (size_t)L.ldy * 4);
   L.rope = take((g.rope_axes[0] + g.rope_axes[1] + g.rope_axes[2]) > 0 ? Nj * (g.head_dim / 2) * 8 : 0);
+  L.partial = take(GEMM_PARTIAL_BYTES);
   L.total = o;
 }
 
@@ -402,6 +407,7 @@ void run_gemm(dit_ctx* c, std::initializer_list<GemmProblem> ps) {
     bytes += 2.0 * ((double)p.M * p.K + (double)p.N * p.K) + (double)p.M * p.N * (p.out_kind == OUT_RESID_F32 ? 8 : p.out_kind == OUT_F32 ? 4 : 2);
   }
   if (!b.n) return;
+  b.partial = c->gemm_partial; b.partial_bytes = c->gemm_partial ? GEMM_PARTIAL_BYTES : 0;
   Scope sc(c, DIT_PROF_GEMM, flop, bytes);
   launch_gemm(c->stream, b);
 }
@@ -625,6 +631,7 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
   HIPCHK(c, hipSetDevice(c->device));
   hipStream_t s = c->stream;
   Run R{c, P, L, c->ws};
+  c->gemm_partial = (float*)(c->ws + L.partial);
   const int Rr = T * n_req;
   {
     // one host image [meta | sigma | a | b], matching the first regions of the workspace; it
@@ -990,6 +997,24 @@ dit_status dit_op_gemm(void* stream, const void* A, int lda, const void* W, int 
   GemmBatch b; b.n = 1; b.total_tiles = 0;
   b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc, gate, gate_stride, row_req);
   launch_gemm((hipStream_t)stream, b, 0);
+  return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
+}
+
+dit_status dit_op_gemm_splitk(void* stream, const void* A, int lda, const void* W, int ldw, const float* bias, int M,
+                              int N, int K, int out_kind, void* out, int ldc, const float* gate, int gate_stride,
+                              const int* row_req, int splits, void* work, size_t work_bytes) {
+  if (!A || !W || !out || !work) return DIT_EINVAL;
+  if (M <= 0 || N <= 0 || K <= 0 || K % 64 || lda < K || ldw < K || ldc < N) return DIT_ESHAPE;
+  if (lda % 8 || ldw % 8) return DIT_ESHAPE;
+  if (out_kind < 0 || out_kind > 3) return DIT_EINVAL;
+  if (ldc % ((out_kind == 1 || out_kind == 3) ? 4 : 8) || ((uintptr_t)out & 15) || ((uintptr_t)work & 15)) return DIT_ESHAPE;
+  if (splits < 1 || splits > K / 64) return DIT_ESHAPE;
+  const size_t tiles = (size_t)((M + 127) / 128) * ((N + 127) / 128);
+  if (work_bytes < tiles * splits * (128 * 128 * 4)) return DIT_ENOMEM;
+  GemmBatch b; b.n = 1; b.total_tiles = 0;
+  b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc, gate, gate_stride, row_req);
+  b.splits = splits; b.partial = (float*)work; b.partial_bytes = work_bytes;
+  launch_gemm((hipStream_t)stream, b, 40128128);
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }
 

@@ -20,7 +20,12 @@ struct GemmProblem {
   const float* gate; int gate_stride; const int* row_req;  // OUT_RESID_F32 only
   int tiles_m, tiles_n, tile_start;                        // filled by the launcher
 };
-struct GemmBatch { int n; int total_tiles; GemmProblem p[3]; };
+struct GemmBatch {
+  int n; int total_tiles; GemmProblem p[3];
+  int splits = 1;                // split-K shares (chosen by the launcher)
+  float* partial = nullptr;      // device scratch for split-K partial tiles, or null (no split-K)
+  size_t partial_bytes = 0;
+};
 
 // Launches up to 3 independent problems in one grid.  Returns the tile shape used (BM*1000+BN).
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile = 0);

@@ -89,8 +89,22 @@ __device__ __forceinline__ void wait_vm() {
   asm volatile("" ::: "memory");
 }
 
+// tile t of a problem -> (tile row, tile column): groups of 8 tile rows, column-major inside
+__device__ __forceinline__ void tile_coords(const GemmProblem& P, int t, int& tm, int& tn) {
+  constexpr int GM = 8;
+  int per = GM * P.tiles_n;
+  int g = t / per, r = t - g * per;
+  int first = g * GM;
+  int gsz = P.tiles_m - first < GM ? P.tiles_m - first : GM;
+  tm = first + r % gsz;
+  tn = r / gsz;
+}
+
 // MODE: 0 = production; 2 and 3 are measurement probes (global->LDS traffic only / LDS reads
-// + MFMAs only) whose output is meaningless.
+// + MFMAs only) whose output is meaningless; 4 = split-K: workgroup b = tile*splits + s walks
+// the s-th share of the k-slabs and leaves its fp32 accumulators, in register order, in chunk
+// b of batch.partial for splitk_reduce_kernel (small-M problems have too few tiles to fill
+// the chip and a lone tile's k-loop runs at global-memory latency per slab).
 template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batch) {
   constexpr int NT = WM * WN * 64;
@@ -112,20 +126,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     int x = bid & 7, idx = bid >> 3, q = nb >> 3, rem = nb & 7;
     bid = x * q + (x < rem ? x : rem) + idx;
   }
+  const int chunk = bid;          // split-K: this workgroup's slot in batch.partial
+  int split = 0;
+  if (MODE == 4) { split = bid % batch.splits; bid /= batch.splits; }
   GemmProblem P = batch.p[0];   // static indices only: keeps the argument block in SGPRs
   if (batch.n > 1 && bid >= batch.p[1].tile_start) P = batch.p[1];
   if (batch.n > 2 && bid >= batch.p[2].tile_start) P = batch.p[2];
-  int t = bid - P.tile_start;
   int tm, tn;
-  {
-    constexpr int GM = 8;
-    int per = GM * P.tiles_n;
-    int g = t / per, r = t - g * per;
-    int first = g * GM;
-    int gsz = P.tiles_m - first < GM ? P.tiles_m - first : GM;
-    tm = first + r % gsz;
-    tn = r / gsz;
-  }
+  tile_coords(P, bid - P.tile_start, tm, tn);
   const int m0 = tm * BM, n0 = tn * BN;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -154,7 +162,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int nk = P.K / BKT;
+  int nk = P.K / BKT;
+  if (MODE == 4) {              // my share of the slabs (shares differ by at most one slab)
+    const int kb = split * nk / batch.splits, ke = (split + 1) * nk / batch.splits;
+    P.A += kb * BKT; P.W += kb * BKT;
+    nk = ke - kb;
+  }
   const int half = lane >> 5;
   // LDS byte offsets of this lane's fragment rows (the chunk index is XORed in per k-step;
   // the key is the same for rows 32 apart)
@@ -235,6 +248,21 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   }
   wait_vm<0, true>();                        // drain the redundant tail loads before LDS is released
   if (MODE == 2) { load_frags(smem, 1, a1, b1); mfma_all(a1, b1); }
+  if (MODE == 4) {
+    // float4 number q = (((wave*TM + i)*TN + j)*4 + g)*64 + lane of the chunk holds
+    // C[32i + 8g + 4*half + 0..3][32j + lane%32] of wave's sub-tile: 1 KB per store instruction
+    float* pc = batch.partial + (size_t)chunk * (BM * BN);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          f32x4 v4 = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+          *(f32x4*)(pc + ((((wave * TM + i) * TN + j) * 4 + g) * 64 + lane) * 4) = v4;
+        }
+    return;
+  }
 
   // ---- epilogue ---------------------------------------------------------------------------
   // acc[i][j][e] is C[32i + 8*(e/4) + 4*half + e%4][32j + lane%32] of the wave's sub-tile: a lane
@@ -326,6 +354,52 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   else epilogue(std::integral_constant<int, OUT_RESID_F32>{});
 }
 
+// Second half of a split-K product: sums the `splits` partial tiles in fixed order (so the
+// result does not depend on which workgroup finished first) and applies the epilogue.  One
+// thread per float4 of the chunk layout written above: 4 consecutive rows of one column, the
+// 32 lanes of a half-wave on 32 consecutive columns.
+template <int BM, int BN, int WM, int WN>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmBatch batch) {
+  constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
+  constexpr int QPT = BM * BN / 4;                 // float4s per tile
+  constexpr int BPT = QPT / 256;                   // workgroups per tile
+  const int tile = blockIdx.x / BPT;
+  const int q = (blockIdx.x % BPT) * 256 + threadIdx.x;
+  GemmProblem P = batch.p[0];
+  if (batch.n > 1 && tile >= batch.p[1].tile_start) P = batch.p[1];
+  if (batch.n > 2 && tile >= batch.p[2].tile_start) P = batch.p[2];
+  int tm, tn;
+  tile_coords(P, tile - P.tile_start, tm, tn);
+  const int lane = q & 63, g = (q >> 6) & 3, j = (q >> 8) % TN, i = (q >> 8) / TN % TM, wave = (q >> 8) / (TN * TM);
+  const int wm = wave / WN, wn = wave % WN;
+  const int n = tn * BN + wn * (BN / WN) + j * 32 + (lane & 31);
+  const int mrow = tm * BM + wm * (BM / WM) + i * 32 + 8 * g + 4 * (lane >> 5);
+  const float* pc = batch.partial + (size_t)tile * batch.splits * (BM * BN) + (size_t)q * 4;
+  f32x4 acc = *(const f32x4*)pc;
+  for (int s = 1; s < batch.splits; ++s) {
+    const f32x4 t4 = *(const f32x4*)(pc + (size_t)s * (BM * BN));
+#pragma unroll
+    for (int c = 0; c < 4; ++c) acc[c] += t4[c];
+  }
+  if (n >= P.N) return;
+  const float bias = P.bias ? P.bias[n] : 0.f;
+#pragma unroll
+  for (int c = 0; c < 4; ++c) {
+    const int m = mrow + c;
+    if (m >= P.M) continue;
+    const float v = acc[c] + bias;
+    const size_t o = (size_t)m * P.ldc + n;
+    if (P.out_kind == OUT_RESID_F32) {
+      const float gt = P.gate ? P.gate[(size_t)(P.row_req ? P.row_req[m] : 0) * P.gate_stride + n] : 1.f;
+      ((float*)P.out)[o] += gt * v;
+    } else if (P.out_kind == OUT_F32) {
+      ((float*)P.out)[o] = v;
+    } else {
+      ((bf16_t*)P.out)[o] = f2bf(P.out_kind == OUT_GELU_BF16 ? gelu_tanh(v) : v);
+    }
+  }
+}
+
 template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE = 0>
 static void launch_t(hipStream_t s, GemmBatch& b) {
   int total = 0;
@@ -345,7 +419,12 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     attr_done = true;
   }
-  hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), lds, s, b);
+  if (MODE == 4) {
+    hipLaunchKernelGGL(kern, dim3(total * b.splits), dim3(WM * WN * 64), lds, s, b);
+    hipLaunchKernelGGL((splitk_reduce_kernel<BM, BN, WM, WN>), dim3(total * (BM * BN / 1024)), dim3(256), 0, s, b);
+  } else {
+    hipLaunchKernelGGL(kern, dim3(total), dim3(WM * WN * 64), lds, s, b);
+  }
 }
 
 // variant codes: BM*1000 + BN, plus
@@ -353,12 +432,36 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
 //   +10000000 k-slab 32 with a 4-stage ring, +20000000 k-slab 32 with a 5-stage ring
 //             (default: k-slab 64, 2 stages)
 //   6256256 / 7256256  measurement probes on the 8-wave 256x256 k-slab-64 kernel
+//   30128128  128x128, k-slab 64, 4-stage ring (one workgroup per CU: for grids below 256 tiles)
+//   40128128  the same as split-K over b.splits shares of K plus the reduction kernel
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
   // Tile choice.  The 256x256 tile (8 waves) halves the L2->LDS traffic per flop of the 128x128
   // tile and is about 25% faster per tile-flop, but one workgroup fills a CU, so its grid runs
   // in rounds of 256 tiles: use it when the last round is at least 3/4 full or there are many
   // rounds; otherwise the 128x128 tile (three workgroups per CU, finer granularity).
   int tile = force_tile;
+  if (tile == 40128128 && (!b.partial || b.splits < 1)) tile = 30128128;   // no scratch: no split
+  if (tile != 40128128) b.splits = 1;
+  if (!tile) {
+    // Few tiles (small M): a lone tile's k-loop runs at memory latency per slab, so keep three
+    // slabs in flight (4-stage ring, one workgroup per CU) and, when K is long enough, split it
+    // over up to 256 workgroups.
+    long long t128 = 0;
+    int min_nk = 1 << 30;
+    for (int i = 0; i < b.n; ++i) {
+      if (b.p[i].M <= 0 || b.p[i].N <= 0) continue;
+      t128 += (long long)((b.p[i].M + 127) / 128) * ((b.p[i].N + 127) / 128);
+      min_nk = b.p[i].K / 64 < min_nk ? b.p[i].K / 64 : min_nk;
+    }
+    if (t128 > 0 && t128 <= 256) {
+      long long sp = 256 / t128;
+      if (sp > min_nk / 4) sp = min_nk / 4;
+      const long long cap = (long long)(b.partial_bytes / (128 * 128 * 4)) / t128;
+      if (sp > cap) sp = cap;
+      if (b.partial && sp >= 2) { b.splits = (int)sp; tile = 40128128; }
+      else tile = 30128128;
+    }
+  }
   if (!tile) {
     long long t256 = 0;
     for (int i = 0; i < b.n; ++i)
@@ -378,6 +481,8 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     case 256128: launch_t<256, 128, 2, 2, 64, 2>(s, b); break;
     case 128256: launch_t<128, 256, 2, 2, 64, 2>(s, b); break;
     case 10128128: launch_t<128, 128, 2, 2, 32, 4>(s, b); break;
+    case 30128128: launch_t<128, 128, 2, 2, 64, 4>(s, b); break;
+    case 40128128: launch_t<128, 128, 2, 2, 64, 4, 4>(s, b); break;
     default: tile = 128128; launch_t<128, 128, 2, 2, 64, 2>(s, b); break;
   }
   return tile;

@@ -67,7 +67,7 @@ def test_set_get_tensor_round_trip(torch, B):
 
 # ---------------------------------------------------------------------------------- GEMM
 @pytest.mark.parametrize("M,N,K", [(300, 384, 256), (1, 256, 64), (517, 1000, 192), (4250, 1536, 1536)])
-@pytest.mark.parametrize("variant", [0, 128128, 10128128, 256256, 1256256, 10256256, 11256256, 20256256, 21256256,
+@pytest.mark.parametrize("variant", [0, 128128, 10128128, 30128128, 256256, 1256256, 10256256, 11256256, 20256256, 21256256,
                                      256128, 128256])
 def test_gemm_against_float64_matmul(torch, B, M, N, K, variant):
     if M > 1000 and variant not in (0, 1256256, 11256256, 128128):
@@ -113,6 +113,53 @@ def test_gemm_gated_residual_epilogue(torch, B):
     torch.cuda.synchronize()
     ref = x0 + gate[row_req][:, 100:100 + N].astype(np.float64) * (A.astype(np.float64) @ W.astype(np.float64).T + bias)
     assert max_abs(dx.cpu().numpy(), ref) < 1e-4
+
+
+@pytest.mark.parametrize("M,N,K,splits", [(218, 384, 1536, 6), (64, 1000, 6144, 7), (1, 256, 64, 1), (300, 130, 320, 5),
+                                          (154, 1536, 1536, 24)])
+def test_gemm_split_k(torch, B, M, N, K, splits):
+    """Split-K form (partial products over shares of K, summed in fixed order): all four
+    epilogues against the float64 product, and bitwise repeatability."""
+    n_req = 3
+    A, W = rnd(1, "A", (M, K)), rnd(2, "W", (N, K), 0.05)
+    bias, gate = rnd(3, "b", (N,), 0.5), synth.gaussian(4, "g", n_req * N).reshape(n_req, N)
+    x0 = synth.gaussian(5, "x", M * N).reshape(M, N)
+    row_req = (np.arange(M) * n_req // M).astype(np.int32)
+    npad = (N + 255) // 256 * 256
+    Wp = np.zeros((npad, K), np.float32); Wp[:N] = W
+    dA, dW = to_dev_bf16(torch, A), to_dev_bf16(torch, Wp)
+    dg, db, dr = torch.from_numpy(gate).cuda(), torch.from_numpy(bias).cuda(), torch.from_numpy(row_req).cuda()
+    wb = ((M + 127) // 128) * ((N + 127) // 128) * splits * 65536
+    work = torch.empty(wb, dtype=torch.uint8, device="cuda")
+    prod = A.astype(np.float64) @ W.astype(np.float64).T + bias
+    ldc = (N + 7) // 8 * 8
+    for kind in (0, 1, 2, 3):
+        outs = []
+        for rep in range(2):
+            work.fill_(0xFF)   # NaN patterns: every partial the reduction reads must have been written
+            if kind == 3:
+                out = torch.zeros((M, ldc), dtype=torch.float32, device="cuda")
+                out[:, :N] = torch.from_numpy(x0).cuda()
+            else:
+                out = torch.full((M, ldc), float("nan"), dtype=torch.float32 if kind == 1 else torch.bfloat16, device="cuda")
+            st = B.dit_op_gemm_splitk(None, dA.data_ptr(), K, dW.data_ptr(), K, db.data_ptr(), M, N, K, kind,
+                                      out.data_ptr(), ldc, dg.data_ptr() if kind == 3 else None, N,
+                                      dr.data_ptr() if kind == 3 else None, splits, work.data_ptr(), wb)
+            assert st == 0
+            torch.cuda.synchronize()
+            outs.append(out[:, :N].to(torch.float32).cpu().numpy())
+        got = outs[0]
+        assert np.array_equal(outs[0], outs[1])
+        want = {0: prod, 1: prod, 2: O.gelu_tanh(prod), 3: x0 + gate[row_req].astype(np.float64) * prod}[kind]
+        tol = 1e-4 if kind in (1, 3) else 2.0 ** -8
+        err = np.abs(got - want) / (np.abs(want) + 1.0)
+        assert np.isfinite(got).all()
+        assert err.max() <= tol, (kind, err.max())
+    # error paths: too many shares, too little scratch
+    assert B.dit_op_gemm_splitk(None, dA.data_ptr(), K, dW.data_ptr(), K, None, M, N, K, 0, out.data_ptr(), ldc,
+                                None, 0, None, K // 64 + 1, work.data_ptr(), wb) != 0
+    assert B.dit_op_gemm_splitk(None, dA.data_ptr(), K, dW.data_ptr(), K, None, M, N, K, 0, out.data_ptr(), ldc,
+                                None, 0, None, splits, work.data_ptr(), wb - 1) != 0
 
 
 # ----------------------------------------------------------------------------- attention
