@@ -82,7 +82,9 @@ const char* dit_last_error(const dit_ctx* ctx);
 /* Bytes of the weight arena (bf16 matrices stored [out][in] with padded leading
  * dimension, fp32 vectors), and of the workspace for a batch and at most `max_steps`
  * steps per dit_sample call (conditioning vectors of all steps are computed up front).
- * dit_workspace_bytes returns 0 on invalid requests. */
+ * dit_workspace_bytes returns 0 on invalid requests.  Limits of one call (DIT_ESHAPE beyond
+ * them): 4096 requests, 2^20 tokens, and tokens x max(3*hidden, hidden + mlp_hidden) < 2^31
+ * (activation matrices are indexed with 32-bit element offsets). */
 size_t dit_weight_bytes(const dit_ctx* ctx);
 size_t dit_workspace_bytes(const dit_ctx* ctx, int n_req, const dit_req* reqs, int max_steps);
 

@@ -228,6 +228,11 @@ dit_status validate_reqs(const dit_ctx* c, int n_req, const dit_req* reqs) {
     tok += (long long)(q.frames / g.patch_t) * (q.height / g.patch_h) * (q.width / g.patch_w) + q.n_cond;
     if (tok > (1 << 20)) return fail(c, DIT_ESHAPE, "more than 2^20 tokens in one call");
   }
+  // The kernels index activation matrices with 32-bit element offsets (row * row stride):
+  // the widest matrix of the step must stay below 2^31 elements.
+  const long long widest = std::max<long long>(3LL * g.hidden, (long long)g.hidden + g.mlp_hidden);
+  if (tok * widest >= (1LL << 31))
+    return fail(c, DIT_ESHAPE, "%lld tokens x %lld columns exceeds the 2^31-element activation limit", tok, widest);
   return DIT_OK;
 }
 

@@ -1,0 +1,179 @@
+#!/usr/bin/env python3
+"""Offline profiler of the Diffuse stage on one MI355X (k = 1, no sequence parallelism).
+
+Two tables, both measured through the library's dit_sample on seeded synthetic requests:
+
+  batch   same-shape dynamic batching (Appendix "Impact of Batch Size" / "Integration with
+          Dynamic Batch"): step latency against batch size B per request shape, and the
+          optimal batch size by the paper's rule: the largest B whose step latency is less
+          than 20 % above that of B = 1.
+  grid    per-request metadata of the offline profiler (Section "Profiler": expected running
+          time and peak memory per request shape): seconds per denoising step, steps/s, and
+          the bytes the stage holds for a request of that shape (weights + workspace), over
+          a resolution grid of a workload family.
+
+    python -m paper_2510_02838_amd.stage_profile batch [--workload sd3] [--res 128,256,512] [--max-batch 32]
+    python -m paper_2510_02838_amd.stage_profile grid  [--workload sd3|flux|wan] [--res ...]
+
+Resolutions are pixels; a latent is res/8 on a side and a patch 2x2, so tokens = (res/16)^2
+plus the text tokens of the workload.  For the video family `--res` lists
+frames x height x width in pixels (latent frames = (frames-1)/4 + 1).  Output: one JSON
+line per table row, then a Markdown table on stderr.
+"""
+import argparse
+import json
+import sys
+import time
+
+import numpy as np
+
+
+def _latent_dims(family_cfg, spec):
+    """'512' -> (1, 32, 32); '81x480x832' -> (21, 60, 104)."""
+    parts = [int(p) for p in str(spec).lower().split("x")]
+    if len(parts) == 1:
+        return (1, parts[0] // 8, parts[0] // 8)
+    if len(parts) == 2:
+        return (1, parts[0] // 8, parts[1] // 8)
+    return ((parts[0] - 1) // 4 + 1, parts[1] // 8, parts[2] // 8)
+
+
+def _tokens(arch, req):
+    f, h, w, nc = req
+    pt, ph, pw = arch["patch"]
+    return (f // pt) * (h // ph) * (w // pw) + nc
+
+
+class Stage:
+    """One model instance; workspace grows to the largest request list seen."""
+
+    def __init__(self, workload, steps):
+        import torch
+        import synth
+        from . import binding as B
+        self.torch, self.synth = torch, synth
+        self.cfg = synth.CONFIGS[workload]
+        self.arch = self.cfg["arch"]
+        self.n_cond = self.cfg["n_cond"]
+        self.steps = steps
+        self.m = B.DiT(self.arch)
+        self.ready = False
+
+    def prepare(self, all_req_lists):
+        """Binds a workspace large enough for every request list, then fills the weights."""
+        need = max(self.m.workspace_bytes(r, self.steps) for r in all_req_lists)
+        big = max(all_req_lists, key=lambda r: self.m.workspace_bytes(r, self.steps))
+        assert need > 0
+        self.m.ensure_workspace(big, self.steps)
+        self.m.init_weights(1, 0.02)
+        self.ready = True
+
+    def time_steps(self, reqs, reps=3):
+        """Best-of-`reps` wall time of one dit_sample of self.steps steps; returns s/step."""
+        torch, synth, arch = self.torch, self.synth, self.arch
+        lat, cond, _ = synth.make_inputs(reqs, arch["latent_ch"], arch["cond_dim"], 1, None)
+        x0 = torch.from_numpy(np.concatenate([a.ravel() for a in lat])).cuda()
+        dc = torch.from_numpy(np.concatenate([c.ravel() for c in cond])).cuda().to(torch.bfloat16)
+        sg = np.stack([synth.default_sigmas(self.steps, 1.0)] * len(reqs))
+        self.m.ensure_workspace(reqs, self.steps)
+        x = x0.clone()
+        self.m.sample(reqs, x, dc, sg)          # warm-up (plan upload, code load)
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(reps):
+            x.copy_(x0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            self.m.sample(reqs, x, dc, sg)
+            torch.cuda.synchronize()
+            best = min(best, time.perf_counter() - t0)
+        if not bool(torch.isfinite(x).all().item()):
+            raise RuntimeError("non-finite latents")
+        return best / self.steps
+
+
+def optimal_batch(latency_by_b, slack=0.20):
+    """Largest batch size whose latency is below (1 + slack) x the latency at B = 1."""
+    base = latency_by_b[1]
+    ok = [b for b, t in sorted(latency_by_b.items()) if t < (1.0 + slack) * base]
+    return max(ok) if ok else 1
+
+
+def run_batch(args):
+    st = Stage(args.workload, args.steps)
+    shapes = [_latent_dims(st.cfg, r) for r in args.res.split(",")]
+    batches = [b for b in (1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64) if b <= args.max_batch]
+    lists = {(s, b): [(s[0], s[1], s[2], st.n_cond)] * b for s in shapes for b in batches}
+    st.prepare(list(lists.values()))
+    rows = []
+    for s, res in zip(shapes, args.res.split(",")):
+        lat = {}
+        for b in batches:
+            lat[b] = st.time_steps(lists[(s, b)])
+            row = {"table": "batch", "workload": args.workload, "res": res, "tokens_per_request": _tokens(st.arch, lists[(s, 1)][0]),
+                   "batch": b, "ms_per_step": lat[b] * 1e3, "latency_vs_b1": lat[b] / lat[1],
+                   "request_steps_per_s": b / lat[b]}
+            rows.append(row)
+            print(json.dumps(row), flush=True)
+        best = optimal_batch(lat)
+        row = {"table": "batch_optimum", "workload": args.workload, "res": res, "optimal_batch": best,
+               "rule": "largest B with step latency < 1.2 x latency(B=1)",
+               "throughput_gain": (best / lat[best]) / (1 / lat[1])}
+        rows.append(row)
+        print(json.dumps(row), flush=True)
+    hdr = "| res | tokens/request | " + " | ".join(f"B={b}" for b in batches) + " | optimal B |"
+    print(hdr, file=sys.stderr)
+    print("|" + "---|" * (len(batches) + 3), file=sys.stderr)
+    for res in args.res.split(","):
+        rr = [r for r in rows if r["table"] == "batch" and r["res"] == res]
+        opt = [r for r in rows if r["table"] == "batch_optimum" and r["res"] == res][0]
+        cells = " | ".join(f"{r['ms_per_step']:.2f} ms (x{r['latency_vs_b1']:.2f})" for r in rr)
+        print(f"| {res} | {rr[0]['tokens_per_request']} | {cells} | {opt['optimal_batch']} |", file=sys.stderr)
+
+
+def run_grid(args):
+    st = Stage(args.workload, args.steps)
+    specs = args.res.split(",")
+    lists = [[_latent_dims(st.cfg, r) + (st.n_cond,)] for r in specs]
+    st.prepare(lists)
+    wbytes = st.m.weight_bytes()
+    print("| request | tokens | s/step | steps/s | workspace GiB | weights GiB |", file=sys.stderr)
+    print("|---|---|---|---|---|---|", file=sys.stderr)
+    for spec, reqs in zip(specs, lists):
+        t = st.time_steps(reqs, reps=2)
+        ws = st.m.workspace_bytes(reqs, args.steps)
+        row = {"table": "grid", "workload": args.workload, "request": spec, "latent": list(reqs[0][:3]),
+               "tokens": _tokens(st.arch, reqs[0]), "s_per_step": t, "steps_per_s": 1.0 / t,
+               "workspace_bytes": ws, "weight_bytes": wbytes, "k": 1}
+        print(json.dumps(row), flush=True)
+        print(f"| {spec} | {row['tokens']} | {t:.5f} | {1.0 / t:.2f} | {ws / 2**30:.3f} | {wbytes / 2**30:.2f} |", file=sys.stderr)
+
+
+DEFAULT_RES = {
+    ("batch", "sd3"): "128,256,512",
+    ("batch", "flux"): "128,256,512",
+    ("grid", "sd3"): "128,256,512,768,1024,1536",
+    ("grid", "flux"): "128,256,512,1024,2048,4096",
+    ("grid", "wan"): "17x480x832,49x480x832,81x480x832,81x720x1280",
+}
+
+
+def main():
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("table", choices=["batch", "grid"])
+    ap.add_argument("--workload", default="sd3", choices=["sd3", "flux", "wan", "tiny"])
+    ap.add_argument("--res", default=None)
+    ap.add_argument("--steps", type=int, default=None, help="denoising steps per timed sample")
+    ap.add_argument("--max-batch", type=int, default=32)
+    args = ap.parse_args()
+    if args.res is None:
+        args.res = DEFAULT_RES.get((args.table, args.workload))
+        if args.res is None:
+            ap.error("give --res for this table/workload")
+    if args.steps is None:
+        args.steps = 8 if args.table == "batch" else (1 if args.workload == "wan" else 2)
+    (run_batch if args.table == "batch" else run_grid)(args)
+
+
+if __name__ == "__main__":
+    main()

@@ -59,7 +59,15 @@ def test_workspace_size_grows_with_batch_and_steps(B):
     assert m.workspace_bytes([(1, 16, 16, 0)], 4) == 0       # empty condition
     assert m.workspace_bytes([], 4) == 0
     assert m.workspace_bytes([(1, 16, 16, 16)], 0) == 0
+    # tokens x widest activation row must stay below 2^31 elements (32-bit offsets in the kernels):
+    # tiny has hidden 256, mlp 1024 -> 1280 columns -> at most 1 677 721 tokens, but also <= 2^20
+    assert m.workspace_bytes([(1, 2048, 2044, 16)], 1) > 0       # 1 044 484 + 16 tokens
+    assert m.workspace_bytes([(1, 2048, 2048, 16)], 1) == 0      # 2^20 + 16 tokens
     m.close()
+    wan = B.DiT(synth.CONFIGS["wan"]["arch"], bind=False)       # 18944 columns -> at most 113 359 tokens
+    assert wan.workspace_bytes([(21, 120, 176, 512)], 1) > 0     # 110 880 + 512 tokens
+    assert wan.workspace_bytes([(21, 120, 180, 512)], 1) == 0    # 113 400 + 512 tokens
+    wan.close()
 
 
 def test_create_rejects_bad_configurations(B):
