@@ -437,8 +437,10 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
   // Tile choice.  The 256x256 tile (8 waves) halves the L2->LDS traffic per flop of the 128x128
   // tile and is about 25% faster per tile-flop, but one workgroup fills a CU, so its grid runs
-  // in rounds of 256 tiles: use it when the last round is at least 3/4 full or there are many
-  // rounds; otherwise the 128x128 tile (three workgroups per CU, finer granularity).
+  // in rounds of 256 tiles: use it from one full round on, unless the last round would hold only
+  // a few tiles (measured over the benchmark shapes: a partly filled last round runs faster
+  // than a full one, lone tiles see less contention); otherwise the 128x128 tile (three
+  // workgroups per CU, finer granularity).
   int tile = force_tile;
   if (tile == 40128128 && (!b.partial || b.splits < 1)) tile = 30128128;   // no scratch: no split
   if (tile != 40128128) b.splits = 1;
@@ -467,7 +469,7 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     for (int i = 0; i < b.n; ++i)
       t256 += (long long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
     const long long rem = t256 % 256;
-    tile = (t256 >= 1024 || (t256 >= 256 && (rem == 0 || rem >= 192))) ? 1256256 : 128128;
+    tile = (t256 >= 1024 || (t256 >= 256 && (rem == 0 || rem >= 32))) ? 1256256 : 128128;
   }
   switch (tile) {
     case 256256: launch_t<256, 256, 2, 2, 64, 2>(s, b); break;

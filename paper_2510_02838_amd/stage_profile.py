@@ -171,7 +171,7 @@ def main():
         if args.res is None:
             ap.error("give --res for this table/workload")
     if args.steps is None:
-        args.steps = 8 if args.table == "batch" else (1 if args.workload == "wan" else 2)
+        args.steps = 8 if args.table == "batch" else (1 if args.workload == "wan" else 4)
     (run_batch if args.table == "batch" else run_grid)(args)
 
 
