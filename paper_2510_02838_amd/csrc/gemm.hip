@@ -469,7 +469,7 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     for (int i = 0; i < b.n; ++i)
       t256 += (long long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
     const long long rem = t256 % 256;
-    tile = (t256 >= 1024 || (t256 >= 256 && (rem == 0 || rem >= 32))) ? 1256256 : 128128;
+    tile = (t256 >= 1024 || (t256 >= 256 && (rem == 0 || rem >= 64))) ? 1256256 : 128128;
   }
   switch (tile) {
     case 256256: launch_t<256, 256, 2, 2, 64, 2>(s, b); break;
