@@ -89,7 +89,10 @@ size_t dit_weight_bytes(const dit_ctx* ctx);
 size_t dit_workspace_bytes(const dit_ctx* ctx, int n_req, const dit_req* reqs, int max_steps);
 
 /* Hands the caller's device buffers to the context (both 256-byte aligned).  The
- * workspace may be re-bound at any time; its contents carry nothing between calls. */
+ * workspace may be re-bound at any time; its contents carry nothing between calls.  The
+ * library keeps a host copy of the largest |gain| of every q/k norm (it bounds the attention
+ * logits), refreshed on the first step after dit_bind, dit_init_weights or dit_set_tensor: a
+ * caller that writes the arena by other means calls dit_bind again afterwards. */
 dit_status dit_bind(dit_ctx* ctx, void* dev_weights, size_t weight_bytes,
                     void* dev_workspace, size_t workspace_bytes);
 
@@ -143,7 +146,9 @@ dit_status dit_sample(dit_ctx* ctx, int n_req, const dit_req* reqs, float* laten
  * (device to device, on the stream) into dev_dst.  Points: "x_txt0", "x_img0",
  * "<blk>.q", "<blk>.k", "<blk>.attn", "<blk>.<stream>.ln1", "<blk>.<stream>.qkv",
  * "<blk>.<stream>.x_attn", "<blk>.<stream>.mlp_act", "<blk>.<stream>.x_out", "final"
- * with <blk> = blk<l> | dbl<l> | sgl<l> and <stream> = txt | img.  `bytes` is the capacity
+ * with <blk> = blk<l> | dbl<l> | sgl<l> and <stream> = txt | img ("<blk>.q" holds the
+ * queries as the attention kernel reads them: multiplied by log2(e)/sqrt(head_dim)).
+ * `bytes` is the capacity
  * of dev_dst; a smaller tensor is copied whole, a larger one fails the step with
  * DIT_ENOMEM.  dit_tap_info reports rows/cols/element size of the last capture. */
 dit_status dit_set_tap(dit_ctx* ctx, const char* point, void* dev_dst, size_t bytes);
@@ -196,12 +201,16 @@ dit_status dit_op_gemm_splitk(void* stream, const void* A, int lda, const void* 
  * rows per segment; vt_off: host int32 [n_seg], multiples of 64, each segment's columns
  * padded to a multiple of 64 with ZEROS (keys past the end are clamped copies whose
  * probabilities only cancel against zero values).  o: dev bf16 [Nq][ldo].  `work` is a dev
- * scratch of at least dit_op_attention_work_bytes(...) bytes. */
+ * scratch of at least dit_op_attention_work_bytes(...) bytes.  q_prescaled != 0: the q rows
+ * were multiplied by log2(e)/sqrt(dh) before rounding to bf16 (what the denoising step's q/k
+ * norm writes; the result is the same function of the unscaled q).  logit_bound (only with
+ * q_prescaled): if 0 < logit_bound <= 60 the caller guarantees |q.k| <= logit_bound for every
+ * prescaled query and key, and the kernel keeps no running max; otherwise pass 0. */
 size_t     dit_op_attention_work_bytes(int n_seg, const int* cu_q);
 dit_status dit_op_attention(void* stream, const void* q, int ldq, const void* k, int ldk,
                             const void* vt, int ldvt, void* o, int ldo, int n_heads, int head_dim,
                             int n_seg, const int* cu_q, const int* cu_k, const int* vt_off,
-                            void* work, size_t work_bytes);
+                            void* work, size_t work_bytes, int q_prescaled, float logit_bound);
 
 /* y = LN(x) * (1 + scale[row_req]) + shift[row_req], LN over the row without affine,
  * eps 1e-6.  x: dev float32 [M][d]; y: dev bf16 [M][d]; shift/scale: dev float32, row r at

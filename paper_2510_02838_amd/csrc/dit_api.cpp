@@ -100,6 +100,9 @@ struct dit_ctx {
   int next_slot = 0;
   int pdim = 0;
   float* gemm_partial = nullptr;   // split-K scratch inside the workspace of the running call
+  // largest |value| of every norm-gain vector (host copy, refreshed lazily after the weights change)
+  std::unordered_map<std::string, float> gain_absmax;
+  bool gain_stats_valid = false;
 };
 
 namespace {
@@ -445,15 +448,30 @@ struct Run {
   const int* ip(size_t meta_off) const { return (const int*)(ws + L.meta + meta_off); }
 };
 
+// log2(e)/sqrt(dh): folded into the q rows by the q/k-norm kernel, so that scores are exponents
+static inline float attn_qscale(int head_dim) { return 1.4426950408889634f / sqrtf((float)head_dim); }
+
+static float gmax(const dit_ctx* c, const std::string& a, const std::string& b = std::string()) {
+  float m = c->gain_absmax.at(a);
+  if (!b.empty()) m = std::max(m, c->gain_absmax.at(b));
+  return m;
+}
+
 void run_attention(dit_ctx* c, const Run& R, const bf16_t* q, int ldq, const bf16_t* k, int ldk, const bf16_t* vt,
                    int ldvt, bf16_t* o, int ldo, const int* cu_q, const int* cu_k, const int* vt_off,
-                   const AttnTile* tiles, int n_tiles, const int* o_row_map, double flop_units) {
+                   const AttnTile* tiles, int n_tiles, const int* o_row_map, double flop_units,
+                   float q_gain_max, float k_gain_max) {
   const dit_config& g = c->cfg;
   AttnArgs a;
   a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.ldvt = ldvt; a.o = o; a.ldo = ldo;
   a.n_heads = g.n_heads; a.head_dim = g.head_dim; a.cu_q = cu_q; a.cu_k = cu_k; a.vt_off = vt_off;
   a.tiles = tiles; a.n_tiles = n_tiles; a.o_row_map = o_row_map; a.q_per_tile = R.P.qb;
-  a.scale_log2 = 1.4426950408889634f / sqrtf((float)g.head_dim);
+  a.scale_log2 = attn_qscale(g.head_dim);
+  // q and k are RMS-normalised per head, so |q'.k| <= (c sqrt(dh) max|g_q|) (sqrt(dh) max|g_k|) with c
+  // the factor folded into q; 2 % on top for the bf16 rounding of both rows.  Below 60 the
+  // attention kernel needs no running max.
+  const float logit_bound = a.scale_log2 * (float)g.head_dim * q_gain_max * k_gain_max * 1.02f;
+  a.mode = logit_bound <= 60.0f ? 2 : 1;
   Scope sc(c, DIT_PROF_ATTN, flop_units * g.hidden, 0);
   launch_attention(c->stream, a);
 }
@@ -484,12 +502,13 @@ dit_status joint_block(dit_ctx* c, const Run& R, const std::string& p, const flo
   {
     Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Ns * d);
     launch_qknorm_rope(c->stream, qkv, 3 * d, Ns, g.n_heads, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, d, 1,
-                       Nt, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"));
+                       Nt, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"), attn_qscale(g.head_dim));
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col), P.Nv_pad, vt, P.Nv_pad);
   }
   TAP(p + ".q", q, P.Nj, d, 2, d); TAP(p + ".k", k, P.Nj, d, 2, d);
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, o, d, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
-                (const AttnTile*)(R.ws + L.meta + P.o_tiles), (int)P.tiles.size(), R.ip(P.o_j2s), P.attn_flop);
+                (const AttnTile*)(R.ws + L.meta + P.o_tiles), (int)P.tiles.size(), R.ip(P.o_j2s), P.attn_flop,
+                gmax(c, pt + ".qnorm.g", pi + ".qnorm.g"), gmax(c, pt + ".knorm.g", pi + ".knorm.g"));
   TAP(p + ".attn", o, Ns, d, 2, d);   // stream order: text rows, then image rows
   run_gemm(c, {mk(o, d, Wm(c, pt + ".proj.w"), Wld(c, pt + ".proj.w"), Wv(c, pt + ".proj.b"), Nt, d, d, OUT_RESID_F32, x, d, mt + 2 * d, MC, rreq),
                mk(o + (size_t)Nt * d, d, Wm(c, pi + ".proj.w"), Wld(c, pi + ".proj.w"), Wv(c, pi + ".proj.b"), Ni, d, d, OUT_RESID_F32, x + (size_t)Nt * d, d, mi + 2 * d, MC, rreq + Nt)});
@@ -529,11 +548,13 @@ dit_status single_block(dit_ctx* c, const Run& R, const std::string& p, const fl
   TAP(p + ".lin1", qkv, Nj, 3 * d, 2, 3 * d);
   {
     Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Nj * d);
-    launch_qknorm_rope(c->stream, qkv, 3 * d, Nj, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1);
+    launch_qknorm_rope(c->stream, qkv, 3 * d, Nj, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
+                       -1, nullptr, nullptr, attn_qscale(g.head_dim));
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col_j), P.Nv_pad, vt, P.Nv_pad);
   }
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, cat, wide, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
-                (const AttnTile*)(R.ws + L.meta + P.o_tiles), (int)P.tiles.size(), nullptr, P.attn_flop);
+                (const AttnTile*)(R.ws + L.meta + P.o_tiles), (int)P.tiles.size(), nullptr, P.attn_flop,
+                gmax(c, p + ".qnorm.g"), gmax(c, p + ".knorm.g"));
   TAP(p + ".attn", cat, Nj, d, 2, wide);
   run_gemm(c, {mk(cat, wide, Wm(c, p + ".lin2.w"), Wld(c, p + ".lin2.w"), Wv(c, p + ".lin2.b"), Nj, d, wide, OUT_RESID_F32, xj, d, m + 2 * d, MC, rreq)});
   TAP(p + ".x_out", xj, Nj, d, 4, d);
@@ -563,11 +584,13 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
   run_gemm(c, {mk(h, d, Wm(c, p + ".qkv.w"), Wld(c, p + ".qkv.w"), Wv(c, p + ".qkv.b"), Ni, 3 * d, d, OUT_BF16, qkv, 3 * d)});
   {
     Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Ni * d);
-    launch_qknorm_rope(c->stream, qkv, 3 * d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1);
+    launch_qknorm_rope(c->stream, qkv, 3 * d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
+                       -1, nullptr, nullptr, attn_qscale(g.head_dim));
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col), P.Nv_pad, vt, P.Nv_pad);
   }
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, o, d, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
-                (const AttnTile*)(R.ws + L.meta + P.o_tiles), (int)P.tiles.size(), nullptr, P.attn_flop);
+                (const AttnTile*)(R.ws + L.meta + P.o_tiles), (int)P.tiles.size(), nullptr, P.attn_flop,
+                gmax(c, p + ".qnorm.g"), gmax(c, p + ".knorm.g"));
   TAP(p + ".attn", o, Ni, d, 2, d);
   run_gemm(c, {mk(o, d, Wm(c, p + ".proj.w"), Wld(c, p + ".proj.w"), Wv(c, p + ".proj.b"), Ni, d, d, OUT_RESID_F32, x, d, e + 2 * d, e6, rreq)});
   TAP(p + ".x_attn", x, Ni, d, 4, d);
@@ -580,12 +603,15 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
                mk(cproj, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), Wv(c, p + ".xkv.b"), Nt, 2 * d, d, OUT_BF16, act, 2 * d)});
   {
     Scope sc(c, DIT_PROF_QKNORM, 0, 4.0 * Ni * d + 8.0 * Nt * d);
-    launch_qknorm_rope(c->stream, qkv, d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".xqnorm.g"), nullptr, nullptr, nullptr, q, nullptr, d, 0, 0);
-    launch_qknorm_rope(c->stream, act, 2 * d, Nt, g.n_heads, g.head_dim, Wv(c, p + ".xknorm.g"), nullptr, nullptr, nullptr, k, nullptr, d, 0, 0);
+    launch_qknorm_rope(c->stream, qkv, d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".xqnorm.g"), nullptr, nullptr, nullptr, q, nullptr, d, 0, 0,
+                       -1, nullptr, nullptr, attn_qscale(g.head_dim));
+    launch_qknorm_rope(c->stream, act, 2 * d, Nt, g.n_heads, g.head_dim, Wv(c, p + ".xknorm.g"), nullptr, nullptr, nullptr, k, nullptr, d, 0, 0,
+                       -1, nullptr, nullptr, 1.f);
     launch_v_transpose(c->stream, act, 2 * d, d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col_x), P.Nvx_pad, vt, P.Nvx_pad);
   }
   run_attention(c, R, q, d, k, d, vt, P.Nvx_pad, o, d, R.ip(P.o_cu_img), R.ip(P.o_cu_txt), R.ip(P.o_vtx_off),
-                (const AttnTile*)(R.ws + L.meta + P.o_xtiles), (int)P.xtiles.size(), nullptr, P.xattn_flop);
+                (const AttnTile*)(R.ws + L.meta + P.o_xtiles), (int)P.xtiles.size(), nullptr, P.xattn_flop,
+                gmax(c, p + ".xqnorm.g"), gmax(c, p + ".xknorm.g"));
   TAP(p + ".xattn", o, Ni, d, 2, d);
   run_gemm(c, {mk(o, d, Wm(c, p + ".xproj.w"), Wld(c, p + ".xproj.w"), Wv(c, p + ".xproj.b"), Ni, d, d, OUT_RESID_F32, x, d)});
   TAP(p + ".x_cross", x, Ni, d, 4, d);
@@ -596,6 +622,25 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
   run_gemm(c, {mk(h, d, Wm(c, p + ".mlp1.w"), Wld(c, p + ".mlp1.w"), Wv(c, p + ".mlp1.b"), Ni, dff, d, OUT_GELU_BF16, act, dff)});
   run_gemm(c, {mk(act, dff, Wm(c, p + ".mlp2.w"), Wld(c, p + ".mlp2.w"), Wv(c, p + ".mlp2.b"), Ni, d, dff, OUT_RESID_F32, x, d, e + 5 * d, e6, rreq)});
   TAP(p + ".x_out", x, Ni, d, 4, d);
+  return DIT_OK;
+}
+
+// Host copy of max|g| of every norm-gain vector (a few KB, device to host, once after the
+// weights changed): the attention launches use it to bound the logits.
+dit_status ensure_gain_stats(dit_ctx* c) {
+  if (c->gain_stats_valid) return DIT_OK;
+  HIPCHK(c, hipStreamSynchronize(c->stream));      // pending weight writes on the context's stream
+  std::vector<float> host;
+  for (const TensorRec& t : c->tensors) {
+    if (t.kind != 2) continue;
+    const size_t n = (size_t)t.rows_in * t.cols_out;
+    host.resize(n);
+    HIPCHK(c, hipMemcpy(host.data(), c->weights + t.off, n * sizeof(float), hipMemcpyDeviceToHost));
+    float m = 0.f;
+    for (float v : host) m = std::isfinite(v) ? std::max(m, std::fabs(v)) : INFINITY;
+    c->gain_absmax[t.name] = m;
+  }
+  c->gain_stats_valid = true;
   return DIT_OK;
 }
 
@@ -634,6 +679,7 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
   if (L.total > c->ws_bytes)
     return fail(c, DIT_ENOMEM, "workspace has %zu bytes, this call needs %zu", c->ws_bytes, L.total);
   HIPCHK(c, hipSetDevice(c->device));
+  if ((st = ensure_gain_stats(c)) != DIT_OK) return st;
   hipStream_t s = c->stream;
   Run R{c, P, L, c->ws};
   c->gemm_partial = (float*)(c->ws + L.partial);
@@ -835,6 +881,7 @@ dit_status dit_bind(dit_ctx* c, void* w, size_t wb, void* ws, size_t wsb) {
   if (((uintptr_t)w & 255) || ((uintptr_t)ws & 255)) return fail(c, DIT_EINVAL, "buffers must be 256-byte aligned");
   if (wb < c->weight_bytes) return fail(c, DIT_ENOMEM, "weight arena has %zu bytes, needs %zu", wb, c->weight_bytes);
   c->weights = (unsigned char*)w; c->ws = (unsigned char*)ws; c->ws_bytes = wsb;
+  c->gain_stats_valid = false;
   return DIT_OK;
 }
 
@@ -855,6 +902,7 @@ dit_status dit_init_weights(dit_ctx* c, uint64_t seed, float std) {
   if (!c->weights) return fail(c, DIT_EINVAL, "dit_bind has not been called");
   if (!(std >= 0.f) || !std::isfinite(std)) return fail(c, DIT_EINVAL, "std must be finite and non-negative");
   HIPCHK(c, hipSetDevice(c->device));
+  c->gain_stats_valid = false;
   HIPCHK(c, hipMemsetAsync(c->weights, 0, c->weight_bytes, c->stream));
   for (const TensorRec& t : c->tensors) {
     const uint64_t key = mix64(seed ^ (fnv1a64(t.name) * 0x9E3779B97F4A7C15ull));
@@ -893,6 +941,7 @@ dit_status dit_set_tensor(dit_ctx* c, const char* name, const float* src, size_t
   if (n != (size_t)t->rows_in * t->cols_out) return fail(c, DIT_ESHAPE, "%s has %d x %d elements", name, t->rows_in, t->cols_out);
   HIPCHK(c, hipSetDevice(c->device));
   HIPCHK(c, hipStreamSynchronize(c->stream));
+  c->gain_stats_valid = false;
   if (t->kind == 0) {
     std::vector<uint16_t> buf((size_t)t->rows_pad * t->ld, 0);   // pads are written as zeros
     for (int i = 0; i < t->rows_in; ++i)
@@ -1044,7 +1093,7 @@ size_t dit_op_attention_work_bytes(int n_seg, const int* cu_q) {
 
 dit_status dit_op_attention(void* stream, const void* q, int ldq, const void* k, int ldk, const void* vt, int ldvt,
                             void* o, int ldo, int n_heads, int head_dim, int n_seg, const int* cu_q, const int* cu_k,
-                            const int* vt_off, void* work, size_t work_bytes) {
+                            const int* vt_off, void* work, size_t work_bytes, int q_prescaled, float logit_bound) {
   if (!q || !k || !vt || !o || !cu_q || !cu_k || !vt_off || !work) return DIT_EINVAL;
   if (n_seg <= 0 || n_heads <= 0 || (head_dim != 64 && head_dim != 128)) return DIT_ESHAPE;
   const int d = n_heads * head_dim;
@@ -1078,7 +1127,8 @@ dit_status dit_op_attention(void* stream, const void* q, int ldq, const void* k,
   a.cu_q = (const int*)w; a.cu_k = (const int*)(w + cu_b); a.vt_off = (const int*)(w + 2 * cu_b);
   a.tiles = (const AttnTile*)(w + 2 * cu_b + vo_b); a.n_tiles = (int)tiles.size(); a.o_row_map = nullptr;
   a.q_per_tile = qb;
-  a.scale_log2 = 1.4426950408889634f / sqrtf((float)head_dim);
+  a.scale_log2 = attn_qscale(head_dim);
+  a.mode = !q_prescaled ? 0 : (logit_bound > 0.f && logit_bound <= 60.f) ? 2 : 1;
   launch_attention(s, a);
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }

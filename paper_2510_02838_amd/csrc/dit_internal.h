@@ -45,6 +45,8 @@ struct AttnArgs {
   // optional scatter of output rows: row j of segment s goes to o_row = map(...)
   const int* o_row_map;         // device [Nq] or null (identity)
   float scale_log2;             // log2(e)/sqrt(dh)
+  int mode;                     // 0: q unscaled, running max; 1: q rows carry scale_log2, running max;
+                                // 2: as 1 and |q.k| <= 60 for every pair: no running max at all
 };
 void launch_attention(hipStream_t s, const AttnArgs& a);
 
@@ -63,7 +65,8 @@ void launch_qknorm_rope(hipStream_t s, const bf16_t* qkv, int ld, int M, int H, 
                         const float* qgain, const float* kgain, const float2* rope,
                         const int* dst_row, bf16_t* qo, bf16_t* ko, int ldo, int k_col_off,
                         int do_k, int split = -1, const float* qgain2 = nullptr,
-                        const float* kgain2 = nullptr);   // rows >= split use the second gains
+                        const float* kgain2 = nullptr,    // rows >= split use the second gains
+                        float qscale = 1.f);              // extra factor on the q output only
 
 // V transpose: v rows [M][ld] at column v_col_off (+h*dh) -> vt[h][c][col], col = vt_col[m].
 // Tiles of 64 destination columns; tile t covers columns 64t..64t+63 and takes source

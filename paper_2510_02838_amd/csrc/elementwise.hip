@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void qknorm_rope_kernel(const bf16_t* __restri
                                                           bf16_t* __restrict__ qo, bf16_t* __restrict__ ko,
                                                           int ldo, int k_col_off, int do_k, int split,
                                                           const float* __restrict__ qgain2,
-                                                          const float* __restrict__ kgain2) {
+                                                          const float* __restrict__ kgain2, float qscale) {
   const int cpr = d >> 3;                                // 16-byte chunks per row
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   const bool ok = idx < (long long)M * cpr;              // (heads never straddle the tail: cpr % (DH/8) == 0)
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(256) void qknorm_rope_kernel(const bf16_t* __restri
     }
 #pragma unroll
     for (int o = DH / 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o);
-    const float r = rsqrtf(ss / (float)DH + 1e-6f);
+    const float r = rsqrtf(ss / (float)DH + 1e-6f) * (which ? 1.f : qscale);
     const float4* gp = (const float4*)((which ? kgain : qgain) + hc);
     const float4 g0 = gp[0], g1 = gp[1];
     const float g[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
@@ -161,14 +161,15 @@ __global__ __launch_bounds__(256) void qknorm_rope_kernel(const bf16_t* __restri
 
 void launch_qknorm_rope(hipStream_t s, const bf16_t* qkv, int ld, int M, int H, int dh, const float* qgain,
                         const float* kgain, const float2* rope, const int* dst_row, bf16_t* qo, bf16_t* ko,
-                        int ldo, int k_col_off, int do_k, int split, const float* qgain2, const float* kgain2) {
+                        int ldo, int k_col_off, int do_k, int split, const float* qgain2, const float* kgain2,
+                        float qscale) {
   if (M == 0) return;
   if (split < 0 || !qgain2) { split = M; qgain2 = qgain; kgain2 = kgain; }
   const int d = H * dh;
   const long long total = (long long)M * (d / 8);
   dim3 g((unsigned)((total + 255) / 256)), b(256);
-  if (dh == 64) hipLaunchKernelGGL(qknorm_rope_kernel<64>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k, split, qgain2, kgain2);
-  else hipLaunchKernelGGL(qknorm_rope_kernel<128>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k, split, qgain2, kgain2);
+  if (dh == 64) hipLaunchKernelGGL(qknorm_rope_kernel<64>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k, split, qgain2, kgain2, qscale);
+  else hipLaunchKernelGGL(qknorm_rope_kernel<128>, g, b, 0, s, qkv, ld, M, d, qgain, kgain, rope, dst_row, qo, ko, ldo, k_col_off, do_k, split, qgain2, kgain2, qscale);
 }
 
 // ---------------------------------------------------------------------------------------

@@ -163,14 +163,17 @@ def test_gemm_split_k(torch, B, M, N, K, splits):
 
 
 # ----------------------------------------------------------------------------- attention
+@pytest.mark.parametrize("mode", [0, 1, 2])
 @pytest.mark.parametrize("dh,H", [(64, 3), (128, 2)])
 @pytest.mark.parametrize("lens", [[1], [64], [65, 7, 300], [410, 1178], [129, 128, 127, 1, 2]])
-def test_attention_against_oracle(torch, B, dh, H, lens):
+def test_attention_against_oracle(torch, B, dh, H, lens, mode):
+    """mode 0: plain q; 1: q carries log2(e)/sqrt(dh), running max kept; 2: as 1 with a logit
+    bound handed over (no running max in the kernel)."""
     d = H * dh
     cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     n = int(cu[-1])
     q, k, v = (rnd(s, nm, (n, d)) for s, nm in ((1, "q"), (2, "k"), (3, "v")))
-    q *= 2.0   # sharper softmax
+    q *= 1.0 if mode == 2 else 2.0   # sharper softmax (mode 2 needs |q.k| log2(e)/sqrt(dh) <= 60)
     q = synth.round_bf16(q)
     vt_off = np.zeros(len(lens), np.int32)
     col = 0
@@ -181,13 +184,21 @@ def test_attention_against_oracle(torch, B, dh, H, lens):
     for s, L in enumerate(lens):
         seg = v[cu[s]:cu[s + 1]].reshape(L, H, dh)
         vt[:, :, vt_off[s]:vt_off[s] + L] = seg.transpose(1, 2, 0)
-    dq, dk, dvt = to_dev_bf16(torch, q), to_dev_bf16(torch, k), to_dev_bf16(torch, vt)
+    qs, bound = q, 0.0
+    if mode:    # the kernel is handed bf16(q * c); the oracle gets that q back unscaled
+        c = np.float32(np.log2(np.e) / np.sqrt(dh))
+        qs = synth.round_bf16((q * c).astype(np.float32))
+        q = qs.astype(np.float64) / np.float64(c)
+        if mode == 2:
+            bound = float(np.linalg.norm(qs.reshape(n, H, dh), axis=2).max() * np.linalg.norm(k.reshape(n, H, dh), axis=2).max())
+            assert bound <= 60.0
+    dq, dk, dvt = to_dev_bf16(torch, qs), to_dev_bf16(torch, k), to_dev_bf16(torch, vt)
     o = torch.full((n, d), float("nan"), dtype=torch.bfloat16, device="cuda")
     ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int))
     wb = B.dit_op_attention_work_bytes(len(lens), ip(cu))
     work = torch.empty(wb, dtype=torch.uint8, device="cuda")
     st = B.dit_op_attention(None, dq.data_ptr(), d, dk.data_ptr(), d, dvt.data_ptr(), col, o.data_ptr(), d, H, dh,
-                            len(lens), ip(cu), ip(cu), ip(vt_off), work.data_ptr(), wb)
+                            len(lens), ip(cu), ip(cu), ip(vt_off), work.data_ptr(), wb, int(mode > 0), bound)
     assert st == 0
     torch.cuda.synchronize()
     got = bf16_to_np(o)
@@ -215,7 +226,7 @@ def test_attention_identical_keys_returns_mean_of_v(torch, B):
     wb = B.dit_op_attention_work_bytes(1, ip(cu))
     work = torch.empty(wb, dtype=torch.uint8, device="cuda")
     assert B.dit_op_attention(None, dq.data_ptr(), d, dk.data_ptr(), d, dvt.data_ptr(), col, o.data_ptr(), d, H, dh,
-                              1, ip(cu), ip(cu), ip(off), work.data_ptr(), wb) == 0
+                              1, ip(cu), ip(cu), ip(off), work.data_ptr(), wb, 0, 0.0) == 0
     torch.cuda.synchronize()
     assert max_abs(bf16_to_np(o), np.tile(v.astype(np.float64).mean(0), (n, 1))) < 1e-2
 
@@ -281,7 +292,9 @@ def test_tiny_config_step_with_intermediates(torch, strong):
     ref = {
         "x_txt0": t["x_txt0"], "x_img0": t["x_img0"],
         "blk0.txt.ln1": t["blk0.txt.ln1"], "blk0.img.ln1": t["blk0.img.ln1"], "blk0.img.qkv": t["blk0.img.qkv"],
-        "blk0.q": t["blk0.q"], "blk0.k": t["blk0.k"], "blk0.attn": t["blk0.attn"],
+        # the library's q rows carry the softmax scale log2(e)/sqrt(head_dim) for its attention kernel
+        "blk0.q": t["blk0.q"] * (np.log2(np.e) / np.sqrt(cfg["arch"]["head_dim"])),
+        "blk0.k": t["blk0.k"], "blk0.attn": t["blk0.attn"],
         "blk0.img.x_attn": t["blk0.img.x_attn"], "blk0.txt.x_attn": t["blk0.txt.x_attn"],
         "blk0.img.mlp_act": t["blk0.img.mlp_act"], "blk0.img.x_out": t["blk0.img.x_out"],
         "blk1.attn": t["blk1.attn"], "blk1.img.x_out": t["blk1.img.x_out"], "final": t["final"],
@@ -384,6 +397,53 @@ def test_family_w_small(torch):
     fg, fo = case.gpu_sample(), case.oracle_sample()
     for r in range(len(reqs)):
         assert rel_l2(fg[r], fo[r]) <= FINAL_REL_L2
+
+
+@pytest.mark.parametrize("family", ["J", "F", "W"])
+def test_attention_mode_follows_the_norm_gains(torch, family):
+    """With small q/k-norm gains the logits are bounded and the attention runs without a running
+    max; after the gains are raised through dit_set_tensor (logit bound far above 2^60 would
+    overflow that form) the same context must switch to the running-max form: both against the
+    oracle, on one context, so that a stale bound shows as inf/NaN or a wrong result."""
+    if family == "J":
+        arch = synth.CONFIGS["tiny"]["arch"]
+        reqs = [(1, 16, 24, 19)]       # (one request: the tap is in stream order, text rows first)
+        taps = ["blk0.attn", "blk1.attn"]
+    elif family == "F":
+        arch = dict(family="F", n_blocks=1, n_single=1, hidden=256, n_heads=2, head_dim=128, mlp_hidden=512,
+                    latent_ch=16, patch=(1, 2, 2), cond_dim=128, rope_axes=(16, 56, 56), rope_theta=10000.0)
+        reqs = [(1, 16, 24, 33)]
+        taps = ["dbl0.attn", "sgl0.attn"]
+    else:
+        arch = dict(family="W", n_blocks=1, n_single=0, hidden=256, n_heads=2, head_dim=128, mlp_hidden=768,
+                    latent_ch=16, patch=(1, 2, 2), cond_dim=128, rope_axes=(44, 42, 42), rope_theta=10000.0)
+        reqs = [(3, 12, 20, 40)]
+        taps = ["blk0.attn", "blk0.xattn"]
+    case = Case(torch, arch, reqs, 2, std=0.06, bias_std=0.1, gain_std=0.1)
+
+    def run(tol):
+        tap_list = [(name, 1 << 24) for name in taps]
+        xg, vg, got = case.gpu_step(0, None, 0, tap_list)
+        xo, vo, otaps = case.oracle_step(0, None, 0, want_taps=True)
+        for r in range(len(reqs)):
+            assert np.isfinite(vg[r]).all()
+            assert rel_l2(vg[r], vo[r]) <= tol, ("v", rel_l2(vg[r], vo[r]))
+        for name in taps:
+            ref = np.concatenate([ot[name] for ot in otaps])
+            assert np.isfinite(got[name]).all(), name
+            assert rel_l2(got[name], ref) <= tol, (name, rel_l2(got[name], ref))
+
+    run(STEP_REL_L2)                          # gains ~1: logit bound 12-20
+    for name in list(case.params):
+        if name.endswith("qnorm.g") or name.endswith("knorm.g"):
+            f = 4.0 if name.endswith("qnorm.g") else 2.0                         # exact in bf16
+            case.params[name] = (case.params[name] * f).astype(np.float32)
+            case.m.set_tensor(name, case.params[name])
+    case.oracle = O.DiTOracle(arch, case.params)
+    # logit bound ~150: needs the running max (2^150 overflows fp32).  Logits eight times larger
+    # also make the softmax eight times more sensitive to the bf16 rounding of q and k, hence
+    # the wider bound; a stale mode would give inf/NaN, not a few per cent.
+    run(5 * STEP_REL_L2)
 
 
 def test_sd3_width_two_blocks_full_tokens(torch):
