@@ -185,6 +185,21 @@ dit_status dit_op_gemm_variant(void* stream, const void* A, int lda, const void*
                                const float* bias, int M, int N, int K, int out_kind, void* out,
                                int ldc, int variant);
 
+/* The QKV product with its q/k epilogue, as the denoising step runs it when no capture point
+ * is registered: C = A W^T + bias; output columns [0, nq) are queries, [nq, nq+nk) keys, the
+ * rest is written as bf16 to out[M][ldc] at its own column (out is not written for q/k
+ * columns).  Per row and head (head_dim 64 or 128 consecutive columns): x <- x / sqrt(mean(x^2)
+ * + 1e-6) * gain, adjacent pairs (2j, 2j+1) rotated by the (cos, sin) in rope[dst][head_dim/2]
+ * (dev float32 pairs, row = destination row; NULL = no rotation), queries times qscale; the
+ * result goes as bf16 to qo / ko (dev, row stride ldo) at row dst_row[m] (dev int32, NULL =
+ * m) and the column inside the q (k) range.  nq, nk multiples of 256; qgain/kgain dev
+ * float32 [head_dim]. */
+dit_status dit_op_gemm_qknorm(void* stream, const void* A, int lda, const void* W, int ldw,
+                              const float* bias, int M, int N, int K, void* out, int ldc,
+                              int nq, int nk, int head_dim, const float* qgain, const float* kgain,
+                              const float* rope, const int* dst_row, void* qo, void* ko, int ldo,
+                              float qscale);
+
 /* As dit_op_gemm, computed as `splits` partial products over disjoint shares of K (each a
  * whole number of 64-wide slabs, 1 <= splits <= K/64) that a second kernel sums in fixed
  * order before the epilogue: the form the denoising step uses when M is small (few tiles,

@@ -59,6 +59,8 @@ _SIGS = {
     "dit_profile_read": (_i, [_vp, _i, C.POINTER(C.c_double), C.POINTER(C.c_longlong),
                               C.POINTER(C.c_double), C.POINTER(C.c_double)]),
     "dit_op_gemm": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp]),
+    "dit_op_gemm_qknorm": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _i, _i, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp,
+                                _i, C.c_float]),
     "dit_op_gemm_splitk": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _i, _vp, _sz]),
     "dit_op_gemm_variant": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _i, _i, _i, _vp, _i, _i]),
     "dit_op_attention_work_bytes": (_sz, [_i, _ip]),

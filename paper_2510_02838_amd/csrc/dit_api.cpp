@@ -402,6 +402,14 @@ GemmProblem mk(const bf16_t* A, int lda, const bf16_t* W, int ldw, const float* 
   p.A = A; p.lda = lda; p.W = W; p.ldw = ldw; p.bias = bias; p.M = M; p.N = N; p.K = K;
   p.out_kind = kind; p.out = out; p.ldc = ldc; p.gate = gate; p.gate_stride = gstride; p.row_req = row_req;
   p.tiles_m = p.tiles_n = p.tile_start = 0;
+  p.qk = QkNorm{};
+  return p;
+}
+// QKV-type product whose first nq (nk) output columns are normalised queries (keys) written to qo (ko)
+GemmProblem with_qknorm(GemmProblem p, int nq, int nk, int head_dim, const float* qgain, const float* kgain,
+                        const float2* rope, const int* dst_row, bf16_t* qo, bf16_t* ko, int ldo, float qscale) {
+  p.out_kind = OUT_QKNORM;
+  p.qk = QkNorm{nq, nk, head_dim, qgain, kgain, rope, dst_row, qo, ko, ldo, qscale};
   return p;
 }
 void run_gemm(dit_ctx* c, std::initializer_list<GemmProblem> ps) {
@@ -452,8 +460,12 @@ struct Run {
 static inline float attn_qscale(int head_dim) { return 1.4426950408889634f / sqrtf((float)head_dim); }
 
 static float gmax(const dit_ctx* c, const std::string& a, const std::string& b = std::string()) {
-  float m = c->gain_absmax.at(a);
-  if (!b.empty()) m = std::max(m, c->gain_absmax.at(b));
+  auto one = [&](const std::string& n) {
+    auto it = c->gain_absmax.find(n);
+    return it == c->gain_absmax.end() ? INFINITY : it->second;   // unknown: no bound, keep the running max
+  };
+  float m = one(a);
+  if (!b.empty()) m = std::max(m, one(b));
   return m;
 }
 
@@ -496,13 +508,23 @@ dit_status joint_block(dit_ctx* c, const Run& R, const std::string& p, const flo
     launch_ln_modulate(c->stream, x, h, Ns, d, mt, mt + d, MC, rreq, nullptr, nullptr, nullptr, Nt, mi, mi + d);
   }
   TAP(pt + ".ln1", h, Nt, d, 2, d); TAP(pi + ".ln1", h + (size_t)Nt * d, Ni, d, 2, d);
-  run_gemm(c, {mk(h, d, Wm(c, pt + ".qkv.w"), Wld(c, pt + ".qkv.w"), Wv(c, pt + ".qkv.b"), Nt, 3 * d, d, OUT_BF16, qkv, 3 * d),
-               mk(h + (size_t)Nt * d, d, Wm(c, pi + ".qkv.w"), Wld(c, pi + ".qkv.w"), Wv(c, pi + ".qkv.b"), Ni, 3 * d, d, OUT_BF16, qkv + (size_t)Nt * 3 * d, 3 * d)});
+  // With no capture point registered the q/k norm, rotary code and softmax scale are the QKV
+  // product's epilogue; with taps every intermediate is materialised by its own kernel.
+  const bool fuse = c->taps.empty();
+  const float qs = attn_qscale(g.head_dim);
+  GemmProblem pq_t = mk(h, d, Wm(c, pt + ".qkv.w"), Wld(c, pt + ".qkv.w"), Wv(c, pt + ".qkv.b"), Nt, 3 * d, d, OUT_BF16, qkv, 3 * d);
+  GemmProblem pq_i = mk(h + (size_t)Nt * d, d, Wm(c, pi + ".qkv.w"), Wld(c, pi + ".qkv.w"), Wv(c, pi + ".qkv.b"), Ni, 3 * d, d, OUT_BF16, qkv + (size_t)Nt * 3 * d, 3 * d);
+  if (fuse) {
+    pq_t = with_qknorm(pq_t, d, d, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, qs);
+    pq_i = with_qknorm(pq_i, d, d, g.head_dim, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"), rope, s2j + Nt, q, k, d, qs);
+  }
+  run_gemm(c, {pq_t, pq_i});
   TAP(pt + ".qkv", qkv, Nt, 3 * d, 2, 3 * d); TAP(pi + ".qkv", qkv + (size_t)Nt * 3 * d, Ni, 3 * d, 2, 3 * d);
   {
-    Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Ns * d);
-    launch_qknorm_rope(c->stream, qkv, 3 * d, Ns, g.n_heads, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, d, 1,
-                       Nt, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"), attn_qscale(g.head_dim));
+    Scope sc(c, DIT_PROF_QKNORM, 0, (fuse ? 4.0 : 12.0) * Ns * d);
+    if (!fuse)
+      launch_qknorm_rope(c->stream, qkv, 3 * d, Ns, g.n_heads, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, d, 1,
+                         Nt, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"), qs);
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col), P.Nv_pad, vt, P.Nv_pad);
   }
   TAP(p + ".q", q, P.Nj, d, 2, d); TAP(p + ".k", k, P.Nj, d, 2, d);
@@ -543,13 +565,17 @@ dit_status single_block(dit_ctx* c, const Run& R, const std::string& p, const fl
     launch_ln_modulate(c->stream, xj, h, Nj, d, m, m + d, MC, rreq, nullptr, nullptr);
   }
   const bf16_t* w1 = Wm(c, p + ".lin1.w"); const int ld1 = Wld(c, p + ".lin1.w"); const float* b1 = Wv(c, p + ".lin1.b");
-  run_gemm(c, {mk(h, d, w1, ld1, b1, Nj, 3 * d, d, OUT_BF16, qkv, 3 * d),
-               mk(h, d, w1 + (size_t)3 * d * ld1, ld1, b1 + 3 * d, Nj, dff, d, OUT_GELU_BF16, cat + d, wide)});
+  const bool fuse = c->taps.empty();          // see joint_block
+  const float qs = attn_qscale(g.head_dim);
+  GemmProblem pq = mk(h, d, w1, ld1, b1, Nj, 3 * d, d, OUT_BF16, qkv, 3 * d);
+  if (fuse) pq = with_qknorm(pq, d, d, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, qs);
+  run_gemm(c, {pq, mk(h, d, w1 + (size_t)3 * d * ld1, ld1, b1 + 3 * d, Nj, dff, d, OUT_GELU_BF16, cat + d, wide)});
   TAP(p + ".lin1", qkv, Nj, 3 * d, 2, 3 * d);
   {
-    Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Nj * d);
-    launch_qknorm_rope(c->stream, qkv, 3 * d, Nj, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
-                       -1, nullptr, nullptr, attn_qscale(g.head_dim));
+    Scope sc(c, DIT_PROF_QKNORM, 0, (fuse ? 4.0 : 12.0) * Nj * d);
+    if (!fuse)
+      launch_qknorm_rope(c->stream, qkv, 3 * d, Nj, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
+                         -1, nullptr, nullptr, qs);
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col_j), P.Nv_pad, vt, P.Nv_pad);
   }
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, cat, wide, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
@@ -581,11 +607,16 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
     Scope sc(c, DIT_PROF_LNMOD, 0, 6.0 * Ni * d);
     launch_ln_modulate(c->stream, x, h, Ni, d, e, e + d, e6, rreq, nullptr, nullptr);
   }
-  run_gemm(c, {mk(h, d, Wm(c, p + ".qkv.w"), Wld(c, p + ".qkv.w"), Wv(c, p + ".qkv.b"), Ni, 3 * d, d, OUT_BF16, qkv, 3 * d)});
+  const bool fuse = c->taps.empty();          // see joint_block
+  const float qs = attn_qscale(g.head_dim);
+  GemmProblem pq = mk(h, d, Wm(c, p + ".qkv.w"), Wld(c, p + ".qkv.w"), Wv(c, p + ".qkv.b"), Ni, 3 * d, d, OUT_BF16, qkv, 3 * d);
+  if (fuse) pq = with_qknorm(pq, d, d, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, qs);
+  run_gemm(c, {pq});
   {
-    Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Ni * d);
-    launch_qknorm_rope(c->stream, qkv, 3 * d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
-                       -1, nullptr, nullptr, attn_qscale(g.head_dim));
+    Scope sc(c, DIT_PROF_QKNORM, 0, (fuse ? 4.0 : 12.0) * Ni * d);
+    if (!fuse)
+      launch_qknorm_rope(c->stream, qkv, 3 * d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
+                         -1, nullptr, nullptr, qs);
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col), P.Nv_pad, vt, P.Nv_pad);
   }
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, o, d, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
@@ -599,14 +630,21 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
     Scope sc(c, DIT_PROF_LNMOD, 0, 6.0 * Ni * d);
     launch_ln_modulate(c->stream, x, h, Ni, d, nullptr, nullptr, 0, nullptr, Wv(c, p + ".xnorm.g"), Wv(c, p + ".xnorm.b"));
   }
-  run_gemm(c, {mk(h, d, Wm(c, p + ".xq.w"), Wld(c, p + ".xq.w"), Wv(c, p + ".xq.b"), Ni, d, d, OUT_BF16, qkv, d),
-               mk(cproj, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), Wv(c, p + ".xkv.b"), Nt, 2 * d, d, OUT_BF16, act, 2 * d)});
+  GemmProblem pxq = mk(h, d, Wm(c, p + ".xq.w"), Wld(c, p + ".xq.w"), Wv(c, p + ".xq.b"), Ni, d, d, OUT_BF16, qkv, d);
+  GemmProblem pxkv = mk(cproj, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), Wv(c, p + ".xkv.b"), Nt, 2 * d, d, OUT_BF16, act, 2 * d);
+  if (fuse) {     // queries only / keys then plain values
+    pxq = with_qknorm(pxq, d, 0, g.head_dim, Wv(c, p + ".xqnorm.g"), nullptr, nullptr, nullptr, q, nullptr, d, qs);
+    pxkv = with_qknorm(pxkv, 0, d, g.head_dim, nullptr, Wv(c, p + ".xknorm.g"), nullptr, nullptr, nullptr, k, d, 1.f);
+  }
+  run_gemm(c, {pxq, pxkv});
   {
-    Scope sc(c, DIT_PROF_QKNORM, 0, 4.0 * Ni * d + 8.0 * Nt * d);
-    launch_qknorm_rope(c->stream, qkv, d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".xqnorm.g"), nullptr, nullptr, nullptr, q, nullptr, d, 0, 0,
-                       -1, nullptr, nullptr, attn_qscale(g.head_dim));
-    launch_qknorm_rope(c->stream, act, 2 * d, Nt, g.n_heads, g.head_dim, Wv(c, p + ".xknorm.g"), nullptr, nullptr, nullptr, k, nullptr, d, 0, 0,
-                       -1, nullptr, nullptr, 1.f);
+    Scope sc(c, DIT_PROF_QKNORM, 0, fuse ? 4.0 * Nt * d : 4.0 * Ni * d + 8.0 * Nt * d);
+    if (!fuse) {
+      launch_qknorm_rope(c->stream, qkv, d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".xqnorm.g"), nullptr, nullptr, nullptr, q, nullptr, d, 0, 0,
+                         -1, nullptr, nullptr, qs);
+      launch_qknorm_rope(c->stream, act, 2 * d, Nt, g.n_heads, g.head_dim, Wv(c, p + ".xknorm.g"), nullptr, nullptr, nullptr, k, nullptr, d, 0, 0,
+                         -1, nullptr, nullptr, 1.f);
+    }
     launch_v_transpose(c->stream, act, 2 * d, d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col_x), P.Nvx_pad, vt, P.Nvx_pad);
   }
   run_attention(c, R, q, d, k, d, vt, P.Nvx_pad, o, d, R.ip(P.o_cu_img), R.ip(P.o_cu_txt), R.ip(P.o_vtx_off),
@@ -1050,6 +1088,24 @@ dit_status dit_op_gemm(void* stream, const void* A, int lda, const void* W, int 
   if (M == 0 || N == 0) return DIT_OK;
   GemmBatch b; b.n = 1; b.total_tiles = 0;
   b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc, gate, gate_stride, row_req);
+  launch_gemm((hipStream_t)stream, b, 0);
+  return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
+}
+
+dit_status dit_op_gemm_qknorm(void* stream, const void* A, int lda, const void* W, int ldw, const float* bias, int M,
+                              int N, int K, void* out, int ldc, int nq, int nk, int head_dim, const float* qgain,
+                              const float* kgain, const float* rope, const int* dst_row, void* qo, void* ko,
+                              int ldo, float qscale) {
+  if (!A || !W || !out) return DIT_EINVAL;
+  if (M <= 0 || N <= 0 || K <= 0 || K % 64 || lda < K || ldw < K || ldc < N) return DIT_ESHAPE;
+  if (lda % 8 || ldw % 8 || ldc % 8 || N % 8 || ((uintptr_t)out & 15)) return DIT_ESHAPE;
+  if (head_dim != 64 && head_dim != 128) return DIT_ESHAPE;
+  if (nq < 0 || nk < 0 || nq % 256 || nk % 256 || nq + nk > N || nq + nk == 0) return DIT_ESHAPE;
+  if ((nq && (!qo || !qgain)) || (nk && (!ko || !kgain))) return DIT_EINVAL;
+  if (ldo % 8 || ldo < std::max(nq, nk) || ((uintptr_t)qo & 15) || ((uintptr_t)ko & 15)) return DIT_ESHAPE;
+  GemmBatch b; b.n = 1; b.total_tiles = 0;
+  b.p[0] = with_qknorm(mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, OUT_BF16, out, ldc), nq, nk,
+                       head_dim, qgain, kgain, (const float2*)rope, dst_row, (bf16_t*)qo, (bf16_t*)ko, ldo, qscale);
   launch_gemm((hipStream_t)stream, b, 0);
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }

@@ -9,7 +9,20 @@ namespace dit {
 typedef uint16_t bf16_t;  // storage type of bf16 tensors
 
 // ---- GEMM ---------------------------------------------------------------------------
-enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_GELU_BF16 = 2, OUT_RESID_F32 = 3 };
+enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_GELU_BF16 = 2, OUT_RESID_F32 = 3, OUT_QKNORM = 4 };
+
+// OUT_QKNORM: output columns [0, nq) are queries and [nq, nq+nk) keys: per head RMS norm (eps
+// 1e-6) times gain, rotary code, queries times qscale, written as bf16 to qo / ko at row
+// dst_row[m] (or m), column = column inside the q (k) range.  Columns from nq+nk on are written
+// as OUT_BF16 to `out`.  nq and nk are multiples of 256, head_dim is 64 or 128.
+struct QkNorm {
+  int nq, nk, head_dim;
+  const float* qgain; const float* kgain;   // [head_dim]
+  const float2* rope;                       // [destination rows][head_dim/2] (cos, sin), or null
+  const int* dst_row;                       // [M] or null
+  bf16_t* qo; bf16_t* ko; int ldo;
+  float qscale;
+};
 
 struct GemmProblem {
   const bf16_t* A; int lda;     // [M][lda] activations
@@ -18,6 +31,7 @@ struct GemmProblem {
   int M, N, K;
   int out_kind; void* out; int ldc;
   const float* gate; int gate_stride; const int* row_req;  // OUT_RESID_F32 only
+  QkNorm qk;                                               // OUT_QKNORM only
   int tiles_m, tiles_n, tile_start;                        // filled by the launcher
 };
 struct GemmBatch {

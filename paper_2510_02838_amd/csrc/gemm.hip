@@ -348,7 +348,95 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
       asm volatile("" ::: "memory");
     }
   };
-  if (P.out_kind == OUT_BF16) epilogue(std::integral_constant<int, OUT_BF16>{});
+  // q/k columns of a QKV product: RMS norm per head, gain, rotary code, scale, scatter by row.
+  // A wave's 64 columns are one head (head_dim 64) or half of one (128: the two waves of a
+  // pair exchange their partial sums of squares through LDS).
+  auto epilogue_qk = [&]() {
+    if constexpr (BN / WN == 64) {
+      constexpr int VEC = 8, LPR = 8, RPI = 8;
+      const QkNorm& Q = P.qk;
+      const int lr = lane / LPR, lc = (lane % LPR) * VEC;
+      const int n = n0 + wn * 64 + lc;               // first of this lane's 8 output columns
+      const bool is_k = n >= Q.nq;
+      const int col_in = is_k ? n - Q.nq : n;        // column inside the q (k) range
+      const int hc = col_in & (Q.head_dim - 1);      // ... inside the head
+      const bool wide = Q.head_dim == 128;
+      const float inv_dh = 1.0f / (float)Q.head_dim;
+      const float osc = is_k ? 1.0f : Q.qscale;
+      float bv[VEC], gv[VEC];
+      {
+        const float* gp = (is_k ? Q.kgain : Q.qgain) + hc;
+        const f32x4 g0 = *(const f32x4*)gp, g1 = *(const f32x4*)(gp + 4);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) { gv[c] = g0[c]; gv[4 + c] = g1[c]; }
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) bv[c] = P.bias ? P.bias[n + c] : 0.f;
+      }
+      float* xch = (float*)(smem + WM * WN * 32 * RS);   // [2][waves][32] partial sums of squares
+      static_assert(WM * WN * 32 * RS + 2 * WM * WN * 32 * 4 <= NS * STAGE, "exchange area fits the ring");
+      bf16_t* dst = is_k ? Q.ko : Q.qo;
+#pragma unroll
+      for (int i = 0; i < TM; ++i) {
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            *(float*)(stg + (8 * (e >> 2) + 4 * half + (e & 3)) * RS + (j * 32 + (lane & 31)) * 4) = acc[i][j][e];
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        float v[4][VEC], ss[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int row = it * RPI + lr;
+          const f32x4 t0 = *(const f32x4*)(stg + row * RS + lc * 4), t1 = *(const f32x4*)(stg + row * RS + (lc + 4) * 4);
+          float s2 = 0.f;
+#pragma unroll
+          for (int c = 0; c < 4; ++c) {
+            v[it][c] = t0[c] + bv[c]; v[it][4 + c] = t1[c] + bv[4 + c];
+            s2 += v[it][c] * v[it][c] + v[it][4 + c] * v[it][4 + c];
+          }
+          s2 += __shfl_xor(s2, 1); s2 += __shfl_xor(s2, 2); s2 += __shfl_xor(s2, 4);
+          ss[it] = s2;
+        }
+        if (wide) {
+          float* mine = xch + ((i & 1) * (WM * WN) + wave) * 32;
+          const float* other = xch + ((i & 1) * (WM * WN) + (wave ^ 1)) * 32;
+          if ((lane % LPR) == 0) {
+#pragma unroll
+            for (int it = 0; it < 4; ++it) mine[it * RPI + lr] = ss[it];
+          }
+          __syncthreads();
+#pragma unroll
+          for (int it = 0; it < 4; ++it) ss[it] += other[it * RPI + lr];
+        }
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int m = m0 + wm * (BM / WM) + i * 32 + it * RPI + lr;
+          if (m >= P.M) continue;
+          const float r = rsqrtf(ss[it] * inv_dh + 1e-6f) * osc;
+          const int drow = Q.dst_row ? Q.dst_row[m] : m;
+          f32x4 c0 = {1.f, 0.f, 1.f, 0.f}, c1 = {1.f, 0.f, 1.f, 0.f};      // (cos, sin) pairs
+          if (Q.rope) {
+            const f32x4* rp = (const f32x4*)(Q.rope + (size_t)drow * (Q.head_dim / 2) + (hc >> 1));
+            c0 = rp[0]; c1 = rp[1];
+          }
+          const float cs[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
+          u32x4 w;
+#pragma unroll
+          for (int pz = 0; pz < 4; ++pz) {
+            const float a = v[it][2 * pz] * r * gv[2 * pz], b = v[it][2 * pz + 1] * r * gv[2 * pz + 1];
+            w[pz] = pack2bf(a * cs[2 * pz] - b * cs[2 * pz + 1], a * cs[2 * pz + 1] + b * cs[2 * pz]);
+          }
+          *(u32x4*)(dst + (size_t)drow * Q.ldo + col_in) = w;
+        }
+        asm volatile("" ::: "memory");
+      }
+    }
+  };
+  if (P.out_kind == OUT_QKNORM) {
+    if (n0 < P.qk.nq + P.qk.nk) epilogue_qk();
+    else epilogue(std::integral_constant<int, OUT_BF16>{});
+  }
+  else if (P.out_kind == OUT_BF16) epilogue(std::integral_constant<int, OUT_BF16>{});
   else if (P.out_kind == OUT_F32) epilogue(std::integral_constant<int, OUT_F32>{});
   else if (P.out_kind == OUT_GELU_BF16) epilogue(std::integral_constant<int, OUT_GELU_BF16>{});
   else epilogue(std::integral_constant<int, OUT_RESID_F32>{});
@@ -460,7 +548,9 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
       if (sp > min_nk / 4) sp = min_nk / 4;
       const long long cap = (long long)(b.partial_bytes / (128 * 128 * 4)) / t128;
       if (sp > cap) sp = cap;
-      if (b.partial && sp >= 2) { b.splits = (int)sp; tile = 40128128; }
+      bool qk = false;                       // the reduction kernel has no q/k-norm epilogue
+      for (int i = 0; i < b.n; ++i) qk = qk || b.p[i].out_kind == OUT_QKNORM;
+      if (b.partial && sp >= 2 && !qk) { b.splits = (int)sp; tile = 40128128; }
       else tile = 30128128;
     }
   }

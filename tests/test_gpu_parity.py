@@ -162,6 +162,66 @@ def test_gemm_split_k(torch, B, M, N, K, splits):
                                 None, 0, None, splits, work.data_ptr(), wb - 1) != 0
 
 
+@pytest.mark.parametrize("M,d,dh,parts", [(300, 256, 64, "qkv"), (517, 512, 128, "qkv"), (70, 256, 128, "q"),
+                                          (4250, 512, 64, "qkv"), (33, 256, 64, "kv")])
+def test_gemm_qknorm_epilogue(torch, B, M, d, dh, parts):
+    """QKV product with the q/k RMS norm, rotary code, scale and row scatter as its epilogue,
+    against the float64 product pushed through the oracle's norm and rotation."""
+    K = 192
+    nq = d if "q" in parts else 0
+    nk = d if "k" in parts else 0
+    nv = d if "v" in parts else 0
+    N = nq + nk + nv
+    A, W = rnd(1, "A", (M, K)), rnd(2, "W", (N, K), 0.05)
+    bias = rnd(3, "b", (N,), 0.5)
+    qg = synth.round_bf16(1.0 + 0.3 * synth.gaussian(4, "qg", dh)).astype(np.float32)
+    kg = synth.round_bf16(1.0 + 0.3 * synth.gaussian(5, "kg", dh)).astype(np.float32)
+    perm = np.random.default_rng(6).permutation(M + 5)[:M].astype(np.int32)       # scatter into M+5 rows
+    ang = synth.gaussian(7, "ang", (M + 5) * (dh // 2)).reshape(M + 5, dh // 2) * 2.0
+    rope = np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)           # [rows][dh/2][2]
+    qscale = np.float32(np.log2(np.e) / np.sqrt(dh))
+    npad = (N + 255) // 256 * 256
+    Wp = np.zeros((npad, K), np.float32); Wp[:N] = W
+    dA, dW = to_dev_bf16(torch, A), to_dev_bf16(torch, Wp)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    db, dqg, dkg, drope, dperm = dev(bias), dev(qg), dev(kg), dev(rope), dev(perm)
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+    qo = torch.full((M + 5, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    ko = torch.full((M + 5, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+    st = B.dit_op_gemm_qknorm(None, dA.data_ptr(), K, dW.data_ptr(), K, db.data_ptr(), M, N, K, out.data_ptr(), N,
+                              nq, nk, dh, dqg.data_ptr(), dkg.data_ptr(), drope.data_ptr(), dperm.data_ptr(),
+                              qo.data_ptr(), ko.data_ptr(), d, float(qscale))
+    assert st == 0
+    torch.cuda.synchronize()
+    prod = A.astype(np.float64) @ W.astype(np.float64).T + bias
+
+    def want(x, gain, scale):
+        H = d // dh
+        y = O.rms_norm(x.reshape(M, H, dh), gain.astype(np.float64))
+        e, o = y[..., 0::2], y[..., 1::2]
+        c, s = np.cos(ang[perm])[:, None, :], np.sin(ang[perm])[:, None, :]
+        r = np.empty_like(y)
+        r[..., 0::2] = e * c - o * s
+        r[..., 1::2] = e * s + o * c
+        return r.reshape(M, d) * scale
+
+    tol = 2.0 ** -7
+    if nq:
+        got = bf16_to_np(qo)[perm]
+        w = want(prod[:, :nq], qg, float(qscale))
+        assert np.isfinite(got).all() and (np.abs(got - w) / (np.abs(w) + 0.05)).max() <= tol
+    if nk:
+        got = bf16_to_np(ko)[perm]
+        w = want(prod[:, nq:nq + nk], kg, 1.0)
+        assert np.isfinite(got).all() and (np.abs(got - w) / (np.abs(w) + 0.25)).max() <= tol
+    if nv:
+        got = bf16_to_np(out)[:, nq + nk:]
+        w = prod[:, nq + nk:]
+        assert np.isfinite(got).all() and (np.abs(got - w) / (np.abs(w) + 1.0)).max() <= 2.0 ** -8
+    untouched = np.setdiff1d(np.arange(M + 5), perm)
+    assert np.isnan(bf16_to_np(qo)[untouched]).all() and np.isnan(bf16_to_np(ko)[untouched]).all()
+
+
 # ----------------------------------------------------------------------------- attention
 @pytest.mark.parametrize("mode", [0, 1, 2])
 @pytest.mark.parametrize("dh,H", [(64, 3), (128, 2)])
