@@ -54,7 +54,8 @@ def test_weights_and_penalties_equal_the_oracles(T):
         tau = float(rng.uniform(0, 3))
         assert np.array_equal(T.reward_weights(t, feas, deadline, tau), DO.reward_weights(t, feas, deadline, tau))
         assert np.array_equal(T.comm_penalty(length), DO.comm_penalty(length))
-    assert T.reward_weights(t, feas, deadline, tau, alpha=2.0).max() > 1000.0 or True
+    # a lower starvation threshold can only raise the reward of late requests
+    assert (T.reward_weights(t, feas, deadline, tau, alpha=2.0) >= T.reward_weights(t, feas, deadline, tau)).all()
 
 
 @pytest.mark.parametrize("seed", range(40))
