@@ -88,3 +88,20 @@ def make_params(shapes, seed, std=0.02, bias_std=0.0, gain_std=0.0):
             raise ValueError(kind)
         out[name] = v.reshape(shape)
     return out
+
+
+# Text encoders of the Encode stage (T5-v1.1-style; the paper's pipelines name T5-XXL, 4.8 B
+# parameters, prompts of 30-500 tokens).  Keys mirror the library's encoder configuration.
+ENCODERS = {
+    "t5_tiny": dict(vocab=1000, d_model=256, n_heads=4, head_dim=64, d_ff=512, n_layers=2),
+    "t5_xxl": dict(vocab=32128, d_model=4096, n_heads=64, head_dim=64, d_ff=10240, n_layers=24),
+}
+
+
+def make_tokens(lengths, vocab, seed=7):
+    """Seeded token ids for prompts of the given lengths: list of int32 arrays."""
+    out = []
+    for r, n in enumerate(lengths):
+        u = gaussian(seed + r, "tokens", n)                      # any seeded real numbers will do
+        out.append((np.floor(np.abs(u) * 1e6).astype(np.int64) % vocab).astype(np.int32))
+    return out
