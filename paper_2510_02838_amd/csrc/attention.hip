@@ -65,6 +65,8 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 // (two waves of different workgroups on a SIMD fall into lock step and do not overlap by
 // themselves).  K and V^T tiles have separate double buffers: at the barrier of iteration kt
 // K(kt+1) and V(kt) have landed, K(kt+2) and V(kt+1) are issued right after it.
+// MODE 3: as mode 0 plus an additive bias looked up by (key position - query position) in a
+// per-head table (the text encoder's relative-position bias; its scale is the caller's).
 // MODE 0: scores are multiplied by log2(e)/sqrt(dh) here; 1: the query rows already carry that
 // factor, so a score is the exponent itself; 2: as 1, and the caller guarantees |q.k| <= 60 for
 // every query/key pair.  In mode 2 no running max is
@@ -170,6 +172,21 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
         st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
       }
     }
+    if constexpr (MODE == 3) {
+      // additive bias by relative position (key - query), read from the per-head table.
+      // Register e of tile t holds key  kt*64 + 32t + 16*(e/8) + 8*half + e%8.
+      const float* bh = a.bias + (size_t)head * (2 * a.bias_L - 1);
+      const int top = 2 * a.bias_L - 2;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int key = kt * KT + 32 * t + 16 * (e >> 3) + 8 * half + (e & 7);
+          int idx = key - qi + a.bias_L - 1;
+          idx = idx < 0 ? 0 : (idx > top ? top : idx);     // keys past the end are clamped copies, masked later
+          st[t][e] += bh[idx];
+        }
+    }
   };
   auto row_max = [&](const f32x16 (&st)[2]) {      // four independent chains, then combined
     float m0 = max3(st[0][0], st[0][1], st[0][2]), m1 = max3(st[0][8], st[0][9], st[0][10]);
@@ -204,7 +221,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
   // One iteration; `sc` holds S(kt) on entry, `sn` receives S(kt+1).  The loop below calls it
   // with the two register sets swapped on alternate tiles instead of copying sn to sc.
   auto step = [&](int kt, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
-    const float c2 = MODE == 0 ? c2_arg : 1.0f;
+    const float c2 = (MODE == 0 || MODE == 3) ? c2_arg : 1.0f;
     // ---- (A) raise the running max only when a row's tile max exceeds it by more than 2^8
     // in the exponent (softmax is shift-invariant, so a stale max is exact as long as nothing
     // overflows: probabilities stay below 2^8); this skips the rescale of O on most tiles.
@@ -320,7 +337,10 @@ void launch_attention(hipStream_t s, const AttnArgs& a) {
     if (w8) { if (d64) launch_t<64, 8, M>(s, a); else launch_t<128, 8, M>(s, a); }             \
     else { if (d64) launch_t<64, 4, M>(s, a); else launch_t<128, 4, M>(s, a); }                \
   } while (0)
-  if (a.mode == 2) ATTN_DISPATCH(2);
+  if (a.mode == 3) {       // encoder attention: sequences are short, 128-query tiles only
+    if (d64) launch_t<64, 4, 3>(s, a); else launch_t<128, 4, 3>(s, a);
+  }
+  else if (a.mode == 2) ATTN_DISPATCH(2);
   else if (a.mode == 1) ATTN_DISPATCH(1);
   else ATTN_DISPATCH(0);
 #undef ATTN_DISPATCH

@@ -60,7 +60,10 @@ struct AttnArgs {
   const int* o_row_map;         // device [Nq] or null (identity)
   float scale_log2;             // log2(e)/sqrt(dh)
   int mode;                     // 0: q unscaled, running max; 1: q rows carry scale_log2, running max;
-                                // 2: as 1 and |q.k| <= 60 for every pair: no running max at all
+                                // 2: as 1 and |q.k| <= 60 for every pair: no running max at all;
+                                // 3: as 0 plus bias[head][key - query + bias_L - 1] added to the scores
+  const float* bias = nullptr;  // mode 3: dev [n_heads][2*bias_L - 1]
+  int bias_L = 0;               // mode 3: no segment is longer than this
 };
 void launch_attention(hipStream_t s, const AttnArgs& a);
 
@@ -120,6 +123,14 @@ void launch_add_rows(hipStream_t s, const float* base, int ld_base, const float*
 // gather rows: dst[dst_row[m]] = src[m] (fp32, d columns); either map may be null
 void launch_copy_rows_f32(hipStream_t s, const float* src, const int* src_row, float* dst,
                           const int* dst_row, int M, int d);
+
+// ---- Encode stage (text encoder) --------------------------------------------------------
+void launch_embed_gather(hipStream_t s, const int* tokens, const float* table, float* x, int M, int d, int vocab);
+// y = x / sqrt(mean(x^2) + 1e-6) * gain; y (bf16) and y32 (fp32) are each optional; d % 256 == 0
+void launch_rmsnorm(hipStream_t s, const float* x, const float* gain, bf16_t* y, float* y32, int M, int d);
+void launch_geglu(hipStream_t s, const bf16_t* a, const bf16_t* b, bf16_t* out, long long n);   // n % 8 == 0
+// bias[h][delta + L - 1] = table[bucket(delta)][h] for delta in (-L, L); table fp32 [32][H]
+void launch_rel_bias_table(hipStream_t s, const float* table, float* bias, int H, int L);
 
 // weights
 void launch_init_matrix(hipStream_t s, bf16_t* w, int rows_out, int cols_in, int ldw,
