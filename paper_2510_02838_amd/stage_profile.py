@@ -12,8 +12,13 @@ Two tables, both measured through the library's dit_sample on seeded synthetic r
           the bytes the stage holds for a request of that shape (weights + workspace), over
           a resolution grid of a workload family.
 
+  encode  the Encode stage (T5-XXL-like text encoder): forward latency against the number of
+          prompts per batch, per prompt length, with the same 20 % rule (the paper: the encoder
+          "can be run with very large batches almost without slowing down").
+
     python -m paper_2510_02838_amd.stage_profile batch [--workload sd3] [--res 128,256,512] [--max-batch 32]
     python -m paper_2510_02838_amd.stage_profile grid  [--workload sd3|flux|wan] [--res ...]
+    python -m paper_2510_02838_amd.stage_profile encode [--encoder t5_xxl] [--lens 32,128,500] [--max-batch 64]
 
 Resolutions are pixels; a latent is res/8 on a side and a patch 2x2, so tokens = (res/16)^2
 plus the text tokens of the workload.  For the video family `--res` lists
@@ -149,6 +154,54 @@ def run_grid(args):
         print(f"| {spec} | {row['tokens']} | {t:.5f} | {1.0 / t:.2f} | {ws / 2**30:.3f} | {wbytes / 2**30:.2f} |", file=sys.stderr)
 
 
+def run_encode(args):
+    import torch
+    import synth
+    from . import encoder as X
+    arch = synth.ENCODERS[args.encoder]
+    lens_list = [int(v) for v in args.lens.split(",")]
+    batches = [b for b in (1, 2, 4, 8, 16, 32, 64, 128) if b <= args.max_batch]
+    m = X.Encoder(arch)
+    m.ensure_workspace([max(lens_list)] * max(batches))
+    m.init_weights(1, 0.02)
+    wbytes = m.weight_bytes()
+    floor_ms = wbytes / 8e12 * 1e3
+    rows = []
+    for n in lens_list:
+        lat = {}
+        for b in batches:
+            lens = [n] * b
+            toks = torch.from_numpy(np.concatenate(synth.make_tokens(lens, arch["vocab"]))).cuda()
+            out = torch.empty((n * b, arch["d_model"]), dtype=torch.bfloat16, device="cuda")
+            m.ensure_workspace(lens)
+            m.forward(lens, toks, out, None)
+            torch.cuda.synchronize()
+            best = float("inf")
+            for _ in range(3):
+                t0 = time.perf_counter()
+                m.forward(lens, toks, out, None)
+                torch.cuda.synchronize()
+                best = min(best, time.perf_counter() - t0)
+            if not bool(torch.isfinite(out.float()).all().item()):
+                raise RuntimeError("non-finite encoder output")
+            lat[b] = best
+            row = {"table": "encode", "encoder": args.encoder, "prompt_tokens": n, "batch": b, "ms": best * 1e3,
+                   "latency_vs_b1": best / lat[1], "prompts_per_s": b / best, "tokens_per_s": b * n / best,
+                   "weight_read_floor_ms": floor_ms}
+            rows.append(row)
+            print(json.dumps(row), flush=True)
+        print(json.dumps({"table": "encode_optimum", "encoder": args.encoder, "prompt_tokens": n,
+                          "optimal_batch": optimal_batch(lat), "rule": "largest B with latency < 1.2 x latency(B=1)"}), flush=True)
+    print(f"weights {wbytes / 2**30:.2f} GiB: one pass over them takes {floor_ms:.2f} ms at 8 TB/s", file=sys.stderr)
+    print("| prompt tokens | " + " | ".join(f"B={b}" for b in batches) + " | optimal B |", file=sys.stderr)
+    print("|" + "---|" * (len(batches) + 2), file=sys.stderr)
+    for n in lens_list:
+        rr = [r for r in rows if r["prompt_tokens"] == n]
+        lat = {r["batch"]: r["ms"] for r in rr}
+        cells = " | ".join(f"{r['ms']:.2f} ms (x{r['latency_vs_b1']:.2f})" for r in rr)
+        print(f"| {n} | {cells} | {optimal_batch(lat)} |", file=sys.stderr)
+
+
 DEFAULT_RES = {
     ("batch", "sd3"): "128,256,512",
     ("batch", "flux"): "128,256,512",
@@ -160,12 +213,18 @@ DEFAULT_RES = {
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("table", choices=["batch", "grid"])
+    ap.add_argument("table", choices=["batch", "grid", "encode"])
+    ap.add_argument("--encoder", default="t5_xxl", choices=["t5_xxl", "t5_tiny"])
+    ap.add_argument("--lens", default="32,128,500")
     ap.add_argument("--workload", default="sd3", choices=["sd3", "flux", "wan", "tiny"])
     ap.add_argument("--res", default=None)
     ap.add_argument("--steps", type=int, default=None, help="denoising steps per timed sample")
-    ap.add_argument("--max-batch", type=int, default=32)
+    ap.add_argument("--max-batch", type=int, default=None)
     args = ap.parse_args()
+    if args.max_batch is None:
+        args.max_batch = 64 if args.table == "encode" else 32
+    if args.table == "encode":
+        return run_encode(args)
     if args.res is None:
         args.res = DEFAULT_RES.get((args.table, args.workload))
         if args.res is None:
