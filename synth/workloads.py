@@ -105,3 +105,11 @@ def make_tokens(lengths, vocab, seed=7):
         u = gaussian(seed + r, "tokens", n)                      # any seeded real numbers will do
         out.append((np.floor(np.abs(u) * 1e6).astype(np.int64) % vocab).astype(np.int32))
     return out
+
+
+# Convolutional decoders of the Decode stage (AutoencoderKL-style).  `channels` are the widths of
+# the up levels in execution order; every level but the last ends with a 2x upsampling.
+DECODERS = {
+    "ae_tiny": dict(latent_ch=16, out_ch=3, channels=(128, 128, 64, 64), n_res=2),
+    "ae_kl": dict(latent_ch=16, out_ch=3, channels=(512, 512, 256, 128), n_res=3),
+}
