@@ -1,0 +1,70 @@
+/* C ABI of the Decode stage on one MI355X: an AutoencoderKL-style convolutional decoder that
+ * maps the latent the Diffuse stage produced to pixels (paper Section 2.1: the latent result is
+ * fed into the Decode stage, a memory-bound decoder; its batch-size figure names AutoEncoderKL).
+ * The paper does not describe the decoder's inside; the published AutoencoderKL decoder is the
+ * reading taken:
+ *
+ *   h = conv3x3(z);  mid: Res, h += proj(attention(GN(h))) (one head over all pixels), Res
+ *   per level: n_res x Res (the first one changes the channel count), then, except after the
+ *   last level, conv3x3(nearest 2x upsampling);  y = conv3x3(SiLU(GN(h)))
+ *   Res(x) = shortcut(x) + conv3x3(SiLU(GN(conv3x3(SiLU(GN(x)))))), shortcut = 1x1 conv when the
+ *   channel count changes; GN = GroupNorm(32 groups, eps 1e-6, affine); all convolutions have a
+ *   bias and zero padding.
+ *
+ * Conventions are those of dit.h.  One latent per call.
+ */
+#ifndef DIT_DECODER_H
+#define DIT_DECODER_H
+
+#include "dit.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dec_ctx dec_ctx;
+
+enum { DEC_MAX_LEVELS = 6 };
+
+typedef struct {
+  int latent_ch;                  /* 1..64                                              */
+  int out_ch;                     /* 1..4                                               */
+  int n_levels;                   /* 1..DEC_MAX_LEVELS                                  */
+  int channels[DEC_MAX_LEVELS];   /* width of each level, each in {64,128,256,512,1024} */
+  int n_res;                      /* residual blocks per level, >= 1                    */
+} dec_config;
+
+dit_status dec_create(const dec_config* cfg, int device, void* hip_stream, dec_ctx** out);
+void       dec_destroy(dec_ctx* ctx);
+const char* dec_last_error(const dec_ctx* ctx);
+
+/* Bytes of the weight arena and of the workspace for a latent of h x w (0 for an invalid size:
+ * h, w >= 1 and (h*w) % 64 == 0 so that the mid-block attention product has whole k-slabs). */
+size_t dec_weight_bytes(const dec_ctx* ctx);
+size_t dec_workspace_bytes(const dec_ctx* ctx, int h, int w);
+dit_status dec_bind(dec_ctx* ctx, void* dev_weights, size_t weight_bytes, void* dev_workspace,
+                    size_t workspace_bytes);
+
+/* Weights ~ N(0, std^2) rounded to bf16 from the counter-based generator of dit_init_weights
+ * (element index = row-major index in the logical [taps*C_in][C_out] matrix), biases 0, gains 1. */
+dit_status dec_init_weights(dec_ctx* ctx, uint64_t seed, float std);
+int        dec_tensor_count(const dec_ctx* ctx);
+dit_status dec_tensor_info(const dec_ctx* ctx, int index, char* name, size_t name_len, int* rows_in,
+                           int* cols_out, int* kind /* 0 matrix, 1 bias, 2 gain */);
+/* Host float32; convolution weights as [taps*C_in][C_out], input index (3*ky + kx)*C_in + c. */
+dit_status dec_set_tensor(dec_ctx* ctx, const char* name, const float* host_src, size_t n);
+dit_status dec_get_tensor(dec_ctx* ctx, const char* name, float* host_dst, size_t n);
+
+/* Decodes one latent.  dev_latent: dev float32 [latent_ch][h][w] (the layout of the Diffuse
+ * stage's latents with one frame); dev_image: dev float32, channels-last
+ * [h*2^(n_levels-1)][w*2^(n_levels-1)][out_ch].  Asynchronous on the context's stream. */
+dit_status dec_forward(dec_ctx* ctx, int h, int w, const float* dev_latent, float* dev_image);
+
+/* Capture points for tests (fp32 channels-last [pixels][C]): "mid.res0", "mid.attn", "up<l>". */
+dit_status dec_set_tap(dec_ctx* ctx, const char* point, void* dev_dst, size_t bytes);
+void       dec_clear_taps(dec_ctx* ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libdit.so")
-SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "encoder.hip", "dit_api.cpp", "enc_api.cpp", "dispatch.cpp"]
+SOURCES = ["gemm.hip", "attention.hip", "elementwise.hip", "encoder.hip", "decoder.hip", "dit_api.cpp", "enc_api.cpp", "dec_api.cpp", "dispatch.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument"]

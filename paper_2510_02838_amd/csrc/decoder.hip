@@ -1,0 +1,230 @@
+// Row-wise kernels of the Decode stage (AutoencoderKL-style convolutional decoder).  Activations
+// are channels-last; the residual stream is fp32 [pixels][C]; inputs of 3x3 convolutions are
+// bf16 images with a one-pixel zero border, [(H+2)*(W+2)][C], so that the convolution is a
+// matrix product with shifted row addresses (gemm.hip) and needs no masking.
+#include "dit_internal.h"
+
+namespace dit {
+
+namespace {
+__device__ __forceinline__ uint16_t d_f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t d_pack2(float a, float b) { return (uint32_t)d_f2bf(a) | ((uint32_t)d_f2bf(b) << 16); }
+__device__ __forceinline__ float d_silu(float x) { return x * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-1.4426950408889634f * x)); }
+// destination row of pixel (y, x): bordered image of width W if pad, plain otherwise
+__device__ __forceinline__ long long dst_pixel(int y, int x, int W, int pad) {
+  return pad ? (long long)(y + 1) * (W + 2) + (x + 1) : (long long)y * W + x;
+}
+}  // namespace
+
+// latent fp32 channels-first [C][H][W] -> bf16 bordered channels-last [(H+2)(W+2)][Cpad], channels
+// from C on are zero (the border is zero from a fill of the whole buffer by the caller)
+__global__ __launch_bounds__(256) void latent_to_image_kernel(const float* __restrict__ z, bf16_t* __restrict__ out,
+                                                              int C, int H, int W, int Cpad) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= (long long)H * W * C) return;
+  const int c = (int)(i % C);
+  const long long p = i / C;
+  const int y = (int)(p / W), x = (int)(p % W);
+  out[dst_pixel(y, x, W, 1) * Cpad + c] = d_f2bf(z[((long long)c * H + y) * W + x]);
+}
+
+void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad) {
+  const long long n = (long long)H * W * C;
+  if (n) hipLaunchKernelGGL(latent_to_image_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, z, out, C, H, W, Cpad);
+}
+
+// zero border of a bordered image [(H+2)(W+2)][C]: rows 0 and H+1, columns 0 and W+1
+__global__ __launch_bounds__(256) void zero_border_kernel(bf16_t* __restrict__ img, int H, int W, int C) {
+  const int o8 = C >> 3;                                   // 16-byte pieces per pixel
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  const long long nb = 2LL * (W + 2) + 2LL * H;            // border pixels
+  if (i >= nb * o8) return;
+  const long long b = i / o8;
+  const int c = (int)(i % o8) * 8;
+  long long pix;
+  if (b < W + 2) pix = b;                                                   // top row
+  else if (b < 2LL * (W + 2)) pix = (long long)(H + 1) * (W + 2) + (b - (W + 2));   // bottom row
+  else { const long long r = b - 2LL * (W + 2); pix = (r / 2 + 1) * (W + 2) + ((r & 1) ? W + 1 : 0); }
+  *(uint4*)(img + pix * C + c) = make_uint4(0, 0, 0, 0);
+}
+void launch_zero_border(hipStream_t s, bf16_t* img, int H, int W, int C) {
+  const long long n = (2LL * (W + 2) + 2LL * H) * (C / 8);
+  if (n) hipLaunchKernelGGL(zero_border_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, img, H, W, C);
+}
+
+// ---- group norm ---------------------------------------------------------------------------
+// pass 1: per chunk of GN_CHUNK pixels, per channel: sum and sum of squares.  A thread owns 4
+// consecutive channels and strides over the chunk's pixels; threads that share channels combine
+// through LDS in a fixed order.  partial: [chunks][C][2].
+constexpr int GN_CHUNK = 256;
+__global__ __launch_bounds__(256) void gn_partial_kernel(const float* __restrict__ x, float* __restrict__ partial,
+                                                         long long P, int C) {
+  extern __shared__ float red[];                // [256 / tpp][C][2]
+  const int qpc = C >> 2;                       // channel quads per pixel
+  const int tid = threadIdx.x;
+  const int quad = tid % qpc, lane_pix = tid / qpc, pix_par = 256 / qpc;   // C <= 1024: qpc <= 256
+  const long long p0 = (long long)blockIdx.x * GN_CHUNK;
+  float s[4] = {0, 0, 0, 0}, q[4] = {0, 0, 0, 0};
+  if (lane_pix < pix_par)
+    for (int pp = lane_pix; pp < GN_CHUNK; pp += pix_par) {
+      const long long p = p0 + pp;
+      if (p >= P) break;
+      const float4 v = ((const float4*)(x + p * C))[quad];
+      s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
+      q[0] += v.x * v.x; q[1] += v.y * v.y; q[2] += v.z * v.z; q[3] += v.w * v.w;
+    }
+  if (lane_pix < pix_par) {
+    float* r = red + ((size_t)lane_pix * C + quad * 4) * 2;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { r[2 * j] = s[j]; r[2 * j + 1] = q[j]; }
+  }
+  __syncthreads();
+  for (int c = tid; c < C; c += 256) {
+    float a = 0.f, b = 0.f;
+    for (int l = 0; l < pix_par; ++l) { a += red[((size_t)l * C + c) * 2]; b += red[((size_t)l * C + c) * 2 + 1]; }
+    partial[((size_t)blockIdx.x * C + c) * 2] = a;
+    partial[((size_t)blockIdx.x * C + c) * 2 + 1] = b;
+  }
+}
+// pass 2: one workgroup per group: chunks and the group's channels summed in fixed order (float64
+// accumulation of the chunk sums); stats[g] = (mean, 1/sqrt(var + eps))
+__global__ __launch_bounds__(256) void gn_finalize_kernel(const float* __restrict__ partial, float2* __restrict__ stats,
+                                                          int chunks, int C, int groups, long long P) {
+  __shared__ double rs[256], rq[256];
+  const int g = blockIdx.x, cpg = C / groups, tid = threadIdx.x;
+  double a = 0.0, b = 0.0;
+  for (int ch = tid; ch < chunks; ch += 256)
+    for (int c = 0; c < cpg; ++c) {
+      const float* pp = partial + ((size_t)ch * C + g * cpg + c) * 2;
+      a += (double)pp[0]; b += (double)pp[1];
+    }
+  rs[tid] = a; rq[tid] = b;
+  __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) {
+    if (tid < o) { rs[tid] += rs[tid + o]; rq[tid] += rq[tid + o]; }
+    __syncthreads();
+  }
+  if (tid == 0) {
+    const double n = (double)P * cpg, mean = rs[0] / n;
+    double var = rq[0] / n - mean * mean;
+    if (var < 0.0) var = 0.0;
+    stats[g] = make_float2((float)mean, (float)(1.0 / sqrt(var + 1e-6)));
+  }
+}
+// pass 3: y = (x - mean_g) rstd_g gamma_c + beta_c, optional SiLU, bf16, bordered or plain rows
+__global__ __launch_bounds__(256) void gn_apply_kernel(const float* __restrict__ x, const float2* __restrict__ stats,
+                                                       const float* __restrict__ gamma, const float* __restrict__ beta,
+                                                       bf16_t* __restrict__ out, int H, int W, int C, int groups,
+                                                       int silu, int pad) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;      // one channel quad
+  const int qpc = C >> 2;
+  if (i >= (long long)H * W * qpc) return;
+  const long long p = i / qpc;
+  const int c = (int)(i % qpc) * 4;
+  const int y = (int)(p / W), xx = (int)(p % W);
+  const float4 v = ((const float4*)(x + p * C))[c >> 2];
+  const float4 ga = *(const float4*)(gamma + c), be = *(const float4*)(beta + c);
+  const int cpg = C / groups;
+  float r[4] = {v.x, v.y, v.z, v.w};
+  const float gg[4] = {ga.x, ga.y, ga.z, ga.w}, bb[4] = {be.x, be.y, be.z, be.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const float2 st = stats[(c + j) / cpg];
+    r[j] = (r[j] - st.x) * st.y * gg[j] + bb[j];
+    if (silu) r[j] = d_silu(r[j]);
+  }
+  uint2 w;
+  w.x = d_pack2(r[0], r[1]); w.y = d_pack2(r[2], r[3]);
+  *(uint2*)(out + dst_pixel(y, xx, W, pad) * C + c) = w;
+}
+
+void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const float* beta, bf16_t* out,
+                       float* partial, float2* stats, int H, int W, int C, int groups, int silu, int pad) {
+  const long long P = (long long)H * W;
+  if (P == 0) return;
+  const int chunks = (int)((P + GN_CHUNK - 1) / GN_CHUNK);
+  const int pix_par = 256 / (C / 4);
+  hipLaunchKernelGGL(gn_partial_kernel, dim3(chunks), dim3(256), (size_t)pix_par * C * 2 * sizeof(float), s, x, partial, P, C);
+  hipLaunchKernelGGL(gn_finalize_kernel, dim3(groups), dim3(256), 0, s, partial, stats, chunks, C, groups, P);
+  const long long n = P * (C / 4);
+  hipLaunchKernelGGL(gn_apply_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, stats, gamma, beta, out, H, W, C, groups, silu, pad);
+}
+size_t group_norm_partial_bytes(long long pixels, int C) {
+  return (size_t)((pixels + GN_CHUNK - 1) / GN_CHUNK) * C * 2 * sizeof(float);
+}
+
+// nearest 2x upsampling of the fp32 stream into a bf16 bordered image: out pixel (y, x) = in (y/2, x/2)
+__global__ __launch_bounds__(256) void upsample_pad_kernel(const float* __restrict__ x, bf16_t* __restrict__ out,
+                                                           int H, int W, int C) {       // H, W: input size
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int qpc = C >> 2;
+  const int H2 = 2 * H, W2 = 2 * W;
+  if (i >= (long long)H2 * W2 * qpc) return;
+  const long long p = i / qpc;
+  const int c = (int)(i % qpc) * 4;
+  const int y = (int)(p / W2), xx = (int)(p % W2);
+  const float4 v = ((const float4*)(x + ((long long)(y >> 1) * W + (xx >> 1)) * C))[c >> 2];
+  uint2 w;
+  w.x = d_pack2(v.x, v.y); w.y = d_pack2(v.z, v.w);
+  *(uint2*)(out + dst_pixel(y, xx, W2, 1) * C + c) = w;
+}
+void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C) {
+  const long long n = (long long)4 * H * W * (C / 4);
+  if (n) hipLaunchKernelGGL(upsample_pad_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, out, H, W, C);
+}
+
+// fp32 -> bf16, 4 elements per thread (plain rows)
+__global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict__ x, bf16_t* __restrict__ out, long long n4) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n4) return;
+  const float4 v = ((const float4*)x)[i];
+  uint2 w;
+  w.x = d_pack2(v.x, v.y); w.y = d_pack2(v.z, v.w);
+  ((uint2*)out)[i] = w;
+}
+void launch_cast_bf16(hipStream_t s, const float* x, bf16_t* out, long long n) {
+  if (n) hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, s, x, out, n / 4);
+}
+
+// row softmax of fp32 scores times `scale`, written as bf16 with row stride ldo; columns from n to
+// ldo are written as zeros.  One workgroup per row, three passes over the row (max, sum, write).
+__global__ __launch_bounds__(256) void softmax_rows_kernel(const float* __restrict__ sc, int lds_, bf16_t* __restrict__ out,
+                                                           int ldo, int n, float scale_log2) {
+  __shared__ float red[256];
+  const float* r = sc + (size_t)blockIdx.x * lds_;
+  const int tid = threadIdx.x;
+  float m = -INFINITY;
+  for (int j = tid; j < n; j += 256) m = fmaxf(m, r[j]);
+  red[tid] = m; __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) { if (tid < o) red[tid] = fmaxf(red[tid], red[tid + o]); __syncthreads(); }
+  m = red[0]; __syncthreads();
+  float s = 0.f;
+  for (int j = tid; j < n; j += 256) s += __builtin_amdgcn_exp2f((r[j] - m) * scale_log2);
+  red[tid] = s; __syncthreads();
+  for (int o = 128; o > 0; o >>= 1) { if (tid < o) red[tid] += red[tid + o]; __syncthreads(); }
+  const float inv = 1.0f / red[0];
+  bf16_t* o_ = out + (size_t)blockIdx.x * ldo;
+  for (int j = tid; j < ldo; j += 256)
+    o_[j] = j < n ? d_f2bf(__builtin_amdgcn_exp2f((r[j] - m) * scale_log2) * inv) : (bf16_t)0;
+}
+void launch_softmax_rows(hipStream_t s, const float* sc, int lds_, bf16_t* out, int ldo, int rows, int n, float scale_log2) {
+  if (rows) hipLaunchKernelGGL(softmax_rows_kernel, dim3(rows), dim3(256), 0, s, sc, lds_, out, ldo, n, scale_log2);
+}
+
+// out[(y*W + x)*C + c] (fp32, channels-last, C small) from the fp32 product rows: plain copy is
+// not needed; the last convolution writes fp32 rows [pixels][ldc] and this kernel compacts them
+__global__ __launch_bounds__(256) void compact_rows_kernel(const float* __restrict__ src, int lds_, float* __restrict__ dst,
+                                                           long long P, int C) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= P * C) return;
+  dst[i] = src[(i / C) * lds_ + (i % C)];
+}
+void launch_compact_rows(hipStream_t s, const float* src, int lds_, float* dst, long long P, int C) {
+  if (P) hipLaunchKernelGGL(compact_rows_kernel, dim3((unsigned)((P * C + 255) / 256)), dim3(256), 0, s, src, lds_, dst, P, C);
+}
+
+}  // namespace dit

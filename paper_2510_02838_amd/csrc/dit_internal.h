@@ -32,6 +32,10 @@ struct GemmProblem {
   int out_kind; void* out; int ldc;
   const float* gate; int gate_stride; const int* row_req;  // OUT_RESID_F32 only
   QkNorm qk;                                               // OUT_QKNORM only
+  // 3x3 convolution as a product (conv_w > 0): A is a channels-last bf16 image with a one-pixel
+  // zero border, [(H+2)*(conv_w+2)][conv_cin]; row m of the product is output pixel (m / conv_w,
+  // m % conv_w), column index k = tap*conv_cin + c with tap = 3*ky + kx; conv_cin % 64 == 0, K = 9*conv_cin.
+  int conv_w = 0, conv_cin = 0;
   int tiles_m, tiles_n, tile_start;                        // filled by the launcher
 };
 struct GemmBatch {
@@ -131,6 +135,23 @@ void launch_rmsnorm(hipStream_t s, const float* x, const float* gain, bf16_t* y,
 void launch_geglu(hipStream_t s, const bf16_t* a, const bf16_t* b, bf16_t* out, long long n);   // n % 8 == 0
 // bias[h][delta + L - 1] = table[bucket(delta)][h] for delta in (-L, L); table fp32 [32][H]
 void launch_rel_bias_table(hipStream_t s, const float* table, float* bias, int H, int L);
+
+// ---- Decode stage (convolutional decoder), channels-last activations ----------------------
+// latent fp32 [C][H][W] -> bf16 bordered image [(H+2)(W+2)][Cpad] (interior only; caller zero-fills)
+void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad);
+void launch_zero_border(hipStream_t s, bf16_t* img, int H, int W, int C);   // C % 8 == 0
+// GroupNorm (eps 1e-6, affine) of the fp32 stream x [H*W][C], optional SiLU, bf16 output with
+// (pad=1) or without a one-pixel border.  C in {64,128,256,512,1024}; partial: scratch of
+// group_norm_partial_bytes; stats: [groups] float2.
+size_t group_norm_partial_bytes(long long pixels, int C);
+void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const float* beta, bf16_t* out,
+                       float* partial, float2* stats, int H, int W, int C, int groups, int silu, int pad);
+// nearest 2x upsampling of x [H*W][C] fp32 into a bf16 bordered image of size 2H x 2W
+void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C);
+void launch_cast_bf16(hipStream_t s, const float* x, bf16_t* out, long long n);     // n % 4 == 0
+// out[r][j] = softmax_j(sc[r][j] * scale) as bf16, j < n; columns n..ldo-1 are set to zero
+void launch_softmax_rows(hipStream_t s, const float* sc, int lds_, bf16_t* out, int ldo, int rows, int n, float scale_log2);
+void launch_compact_rows(hipStream_t s, const float* src, int lds_, float* dst, long long P, int C);
 
 // weights
 void launch_init_matrix(hipStream_t s, bf16_t* w, int rows_out, int cols_in, int ldw,

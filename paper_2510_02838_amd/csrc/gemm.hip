@@ -146,7 +146,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   for (int i = 0; i < LA; ++i) {
     int q = i * NT + tid, r = q / CPR, pc = q % CPR, c = pc ^ swz_key<BKT>(r);
     int m = m0 + r; if (m >= P.M) m = P.M - 1;            // clamp: rows past M are never stored
-    ga[i] = (uint32_t)m * (uint32_t)P.lda + c * 8;
+    if (P.conv_w > 0) {      // top-left pixel of the 3x3 window in the bordered image
+      const int y = m / P.conv_w, x = m - y * P.conv_w;
+      ga[i] = (uint32_t)(y * (P.conv_w + 2) + x) * (uint32_t)P.conv_cin + c * 8;
+    } else {
+      ga[i] = (uint32_t)m * (uint32_t)P.lda + c * 8;
+    }
   }
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
@@ -182,7 +187,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   auto issue = [&](int kt) {
     unsigned char* dA = smem + (kt % NS) * STAGE;
     const int ks = (kt < nk ? kt : nk - 1) * BKT;
-    const bf16_t* Ak = P.A + ks;
+    int ka = ks;             // A-side offset of the slab
+    if (P.conv_w > 0) {      // slab = 64 channels of one tap (ky, kx): shift by ky rows and kx pixels
+      const int tap = ks / P.conv_cin, c0 = ks - tap * P.conv_cin, ky = tap / 3, kx = tap - 3 * ky;
+      ka = (ky * (P.conv_w + 2) + kx) * P.conv_cin + c0;
+    }
+    const bf16_t* Ak = P.A + ka;
     const bf16_t* Wk = P.W + ks;
     unsigned char* dB = dA + OFFB;
 #pragma unroll
@@ -549,7 +559,7 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
       const long long cap = (long long)(b.partial_bytes / (128 * 128 * 4)) / t128;
       if (sp > cap) sp = cap;
       bool qk = false;                       // the reduction kernel has no q/k-norm epilogue
-      for (int i = 0; i < b.n; ++i) qk = qk || b.p[i].out_kind == OUT_QKNORM;
+      for (int i = 0; i < b.n; ++i) qk = qk || b.p[i].out_kind == OUT_QKNORM || b.p[i].conv_w > 0;   // (nor the split A offsets a convolution's)
       if (b.partial && sp >= 2 && !qk) { b.splits = (int)sp; tile = 40128128; }
       else tile = 30128128;
     }
