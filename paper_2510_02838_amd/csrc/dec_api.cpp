@@ -113,8 +113,16 @@ struct Layout {
 };
 constexpr size_t PARTIAL_BYTES = (size_t)256 * 128 * 128 * 4;
 
-bool size_ok(int h, int w) {
-  return h >= 1 && w >= 1 && h <= 4096 && w <= 4096 && ((long long)h * w) % 64 == 0 && (long long)h * w <= 65536;
+// latent sides 1..4096, h*w a multiple of 64 (whole k-slabs in the attention products) and at
+// most 65536 (the score matrix is held whole); the final image at most 65535 rows and, with its
+// border and the widest level, below 2^32 elements (32-bit offsets in the kernels)
+bool size_ok(const dec_ctx* c, int h, int w) {
+  if (!(h >= 1 && w >= 1 && h <= 4096 && w <= 4096 && ((long long)h * w) % 64 == 0 && (long long)h * w <= 65536)) return false;
+  const int up = 1 << (c->cfg.n_levels - 1);
+  int maxc = 64;
+  for (int l = 0; l < c->cfg.n_levels; ++l) maxc = std::max(maxc, c->cfg.channels[l]);
+  const long long Hf = (long long)h * up, Wf = (long long)w * up;
+  return Hf <= 65535 && (Hf + 2) * (Wf + 2) * maxc < (1LL << 32) && Hf * Wf < (1LL << 31) / 4;
 }
 
 void plan(const dec_ctx* c, int h, int w, Layout& L) {
@@ -271,7 +279,7 @@ void dec_destroy(dec_ctx* c) {
 const char* dec_last_error(const dec_ctx* c) { return c ? c->err.c_str() : "null context"; }
 size_t dec_weight_bytes(const dec_ctx* c) { return c ? c->weight_bytes : 0; }
 size_t dec_workspace_bytes(const dec_ctx* c, int h, int w) {
-  if (!c || !size_ok(h, w)) return 0;
+  if (!c || !size_ok(c, h, w)) return 0;
   Layout L;
   plan(c, h, w, L);
   return L.total;
@@ -375,7 +383,8 @@ dit_status dec_forward(dec_ctx* c, int h, int w, const float* latent, float* ima
   if (!c) return DIT_EINVAL;
   if (!c->weights || !c->ws) return dfail(c, DIT_EINVAL, "dec_bind has not been called");
   if (!latent || !image) return dfail(c, DIT_EINVAL, "null latent or image");
-  if (!size_ok(h, w)) return dfail(c, DIT_ESHAPE, "latent %d x %d: sides 1..4096, pixel count a multiple of 64 and at most 65536", h, w);
+  if (!size_ok(c, h, w))
+    return dfail(c, DIT_ESHAPE, "latent %d x %d: sides 1..4096, pixel count a multiple of 64 and at most 65536, image below 2^32 elements per level", h, w);
   const dec_config& g = c->cfg;
   DHIP(c, hipSetDevice(c->device));
   Layout L;

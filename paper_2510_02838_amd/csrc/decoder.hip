@@ -59,25 +59,37 @@ void launch_zero_border(hipStream_t s, bf16_t* img, int H, int W, int C) {
 // ---- group norm ---------------------------------------------------------------------------
 // pass 1: per chunk of GN_CHUNK pixels, per channel: sum and sum of squares.  A thread owns 4
 // consecutive channels and strides over the chunk's pixels; threads that share channels combine
-// through LDS in a fixed order.  partial: [chunks][C][2].
+// through LDS in a fixed order.  partial: [chunks][C][2].  C is a power of two in 64..1024.
 constexpr int GN_CHUNK = 256;
 __global__ __launch_bounds__(256) void gn_partial_kernel(const float* __restrict__ x, float* __restrict__ partial,
-                                                         long long P, int C) {
-  extern __shared__ float red[];                // [256 / tpp][C][2]
-  const int qpc = C >> 2;                       // channel quads per pixel
+                                                         long long P, int C, int qsh) {
+  extern __shared__ float red[];                // [pix_par][C][2]
+  const int qpc = C >> 2;                       // channel quads per pixel = 1 << qsh
   const int tid = threadIdx.x;
-  const int quad = tid % qpc, lane_pix = tid / qpc, pix_par = 256 / qpc;   // C <= 1024: qpc <= 256
+  const int quad = tid & (qpc - 1), lane_pix = tid >> qsh, pix_par = 256 >> qsh;
   const long long p0 = (long long)blockIdx.x * GN_CHUNK;
   float s[4] = {0, 0, 0, 0}, q[4] = {0, 0, 0, 0};
-  if (lane_pix < pix_par)
-    for (int pp = lane_pix; pp < GN_CHUNK; pp += pix_par) {
-      const long long p = p0 + pp;
-      if (p >= P) break;
-      const float4 v = ((const float4*)(x + p * C))[quad];
+  const float4* xp = (const float4*)(x + p0 * C) + quad;
+  if (p0 + GN_CHUNK <= P) {
+    // whole chunk: four independent loads in flight per thread
+    for (int pp = lane_pix; pp < GN_CHUNK; pp += 4 * pix_par) {
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = xp[(size_t)(pp + u * pix_par) * qpc];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        s[0] += v[u].x; s[1] += v[u].y; s[2] += v[u].z; s[3] += v[u].w;
+        q[0] += v[u].x * v[u].x; q[1] += v[u].y * v[u].y; q[2] += v[u].z * v[u].z; q[3] += v[u].w * v[u].w;
+      }
+    }
+  } else {
+    for (int pp = lane_pix; pp < GN_CHUNK && p0 + pp < P; pp += pix_par) {
+      const float4 v = xp[(size_t)pp * qpc];
       s[0] += v.x; s[1] += v.y; s[2] += v.z; s[3] += v.w;
       q[0] += v.x * v.x; q[1] += v.y * v.y; q[2] += v.z * v.z; q[3] += v.w * v.w;
     }
-  if (lane_pix < pix_par) {
+  }
+  {
     float* r = red + ((size_t)lane_pix * C + quad * 4) * 2;
 #pragma unroll
     for (int j = 0; j < 4; ++j) { r[2 * j] = s[j]; r[2 * j + 1] = q[j]; }
@@ -115,31 +127,32 @@ __global__ __launch_bounds__(256) void gn_finalize_kernel(const float* __restric
     stats[g] = make_float2((float)mean, (float)(1.0 / sqrt(var + 1e-6)));
   }
 }
-// pass 3: y = (x - mean_g) rstd_g gamma_c + beta_c, optional SiLU, bf16, bordered or plain rows
+// pass 3: y = (x - mean_g) rstd_g gamma_c + beta_c, optional SiLU, bf16, bordered or plain rows.
+// One image row per blockIdx.y; a thread takes 8 consecutive channels of one pixel.
 __global__ __launch_bounds__(256) void gn_apply_kernel(const float* __restrict__ x, const float2* __restrict__ stats,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                       bf16_t* __restrict__ out, int H, int W, int C, int groups,
+                                                       bf16_t* __restrict__ out, int W, int C, int osh, int gsh,
                                                        int silu, int pad) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;      // one channel quad
-  const int qpc = C >> 2;
-  if (i >= (long long)H * W * qpc) return;
-  const long long p = i / qpc;
-  const int c = (int)(i % qpc) * 4;
-  const int y = (int)(p / W), xx = (int)(p % W);
-  const float4 v = ((const float4*)(x + p * C))[c >> 2];
-  const float4 ga = *(const float4*)(gamma + c), be = *(const float4*)(beta + c);
-  const int cpg = C / groups;
-  float r[4] = {v.x, v.y, v.z, v.w};
-  const float gg[4] = {ga.x, ga.y, ga.z, ga.w}, bb[4] = {be.x, be.y, be.z, be.w};
+  const int i = blockIdx.x * 256 + threadIdx.x;      // unit of 8 channels inside the row
+  const int opc = C >> 3;                            // = 1 << osh
+  if (i >= W * opc) return;
+  const int y = blockIdx.y, xx = i >> osh, c = (i & (opc - 1)) * 8;
+  const float* xr = x + ((size_t)y * W + xx) * C + c;
+  const float4 v0 = *(const float4*)xr, v1 = *(const float4*)(xr + 4);
+  const float4 g0 = *(const float4*)(gamma + c), g1 = *(const float4*)(gamma + c + 4);
+  const float4 b0 = *(const float4*)(beta + c), b1 = *(const float4*)(beta + c + 4);
+  float r[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
+  const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
+  const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    const float2 st = stats[(c + j) / cpg];
+  for (int j = 0; j < 8; ++j) {
+    const float2 st = stats[(c + j) >> gsh];
     r[j] = (r[j] - st.x) * st.y * gg[j] + bb[j];
     if (silu) r[j] = d_silu(r[j]);
   }
-  uint2 w;
-  w.x = d_pack2(r[0], r[1]); w.y = d_pack2(r[2], r[3]);
-  *(uint2*)(out + dst_pixel(y, xx, W, pad) * C + c) = w;
+  uint4 w;
+  w.x = d_pack2(r[0], r[1]); w.y = d_pack2(r[2], r[3]); w.z = d_pack2(r[4], r[5]); w.w = d_pack2(r[6], r[7]);
+  *(uint4*)(out + dst_pixel(y, xx, W, pad) * C + c) = w;
 }
 
 void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const float* beta, bf16_t* out,
@@ -147,11 +160,15 @@ void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const 
   const long long P = (long long)H * W;
   if (P == 0) return;
   const int chunks = (int)((P + GN_CHUNK - 1) / GN_CHUNK);
-  const int pix_par = 256 / (C / 4);
-  hipLaunchKernelGGL(gn_partial_kernel, dim3(chunks), dim3(256), (size_t)pix_par * C * 2 * sizeof(float), s, x, partial, P, C);
+  int csh = 0;
+  while ((1 << csh) < C) ++csh;                  // C = 1 << csh
+  int gsh = 0;
+  while ((groups << gsh) < C) ++gsh;             // channels per group = 1 << gsh
+  const int pix_par = 256 >> (csh - 2);
+  hipLaunchKernelGGL(gn_partial_kernel, dim3(chunks), dim3(256), (size_t)pix_par * C * 2 * sizeof(float), s, x, partial, P, C, csh - 2);
   hipLaunchKernelGGL(gn_finalize_kernel, dim3(groups), dim3(256), 0, s, partial, stats, chunks, C, groups, P);
-  const long long n = P * (C / 4);
-  hipLaunchKernelGGL(gn_apply_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, stats, gamma, beta, out, H, W, C, groups, silu, pad);
+  const int units = W * (C >> 3);
+  hipLaunchKernelGGL(gn_apply_kernel, dim3((units + 255) / 256, H), dim3(256), 0, s, x, stats, gamma, beta, out, W, C, csh - 3, gsh, silu, pad);
 }
 size_t group_norm_partial_bytes(long long pixels, int C) {
   return (size_t)((pixels + GN_CHUNK - 1) / GN_CHUNK) * C * 2 * sizeof(float);
@@ -211,8 +228,58 @@ __global__ __launch_bounds__(256) void softmax_rows_kernel(const float* __restri
   for (int j = tid; j < ldo; j += 256)
     o_[j] = j < n ? d_f2bf(__builtin_amdgcn_exp2f((r[j] - m) * scale_log2) * inv) : (bf16_t)0;
 }
+// the same with the row held in registers between the passes (n <= 256 * 4 * NV, n % 4 == 0,
+// ldo % 4 == 0): one read of the scores instead of three
+template <int NV>
+__global__ __launch_bounds__(256) void softmax_rows_reg_kernel(const float* __restrict__ sc, int lds_, bf16_t* __restrict__ out,
+                                                               int ldo, int n, float scale_log2) {
+  __shared__ float red[4];
+  const float4* r = (const float4*)(sc + (size_t)blockIdx.x * lds_);
+  const int tid = threadIdx.x, n4 = n >> 2;
+  float4 v[NV];
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int j = i * 256 + tid;
+    v[i] = j < n4 ? r[j] : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    m = fmaxf(fmaxf(m, fmaxf(v[i].x, v[i].y)), fmaxf(v[i].z, v[i].w));
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) m = fmaxf(m, __shfl_xor(m, o));
+  if ((tid & 63) == 0) red[tid >> 6] = m;
+  __syncthreads();
+  m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  __syncthreads();
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    v[i].x = __builtin_amdgcn_exp2f((v[i].x - m) * scale_log2); v[i].y = __builtin_amdgcn_exp2f((v[i].y - m) * scale_log2);
+    v[i].z = __builtin_amdgcn_exp2f((v[i].z - m) * scale_log2); v[i].w = __builtin_amdgcn_exp2f((v[i].w - m) * scale_log2);
+    s += (v[i].x + v[i].y) + (v[i].z + v[i].w);          // (exp2(-inf) = 0 past the row's end)
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
+  if ((tid & 63) == 0) red[tid >> 6] = s;
+  __syncthreads();
+  const float inv = 1.0f / ((red[0] + red[1]) + (red[2] + red[3]));
+  uint2* o_ = (uint2*)(out + (size_t)blockIdx.x * ldo);
+  const int o4 = ldo >> 2;
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int j = i * 256 + tid;
+    if (j < o4) {
+      uint2 w;
+      w.x = d_pack2(v[i].x * inv, v[i].y * inv); w.y = d_pack2(v[i].z * inv, v[i].w * inv);
+      o_[j] = w;                                         // zeros from n to ldo
+    }
+  }
+}
 void launch_softmax_rows(hipStream_t s, const float* sc, int lds_, bf16_t* out, int ldo, int rows, int n, float scale_log2) {
-  if (rows) hipLaunchKernelGGL(softmax_rows_kernel, dim3(rows), dim3(256), 0, s, sc, lds_, out, ldo, n, scale_log2);
+  if (!rows) return;
+  const bool vec = n % 4 == 0 && ldo % 4 == 0 && lds_ % 4 == 0 && ldo <= 16384 && n <= ldo;
+  if (vec && ldo <= 4096) hipLaunchKernelGGL(softmax_rows_reg_kernel<4>, dim3(rows), dim3(256), 0, s, sc, lds_, out, ldo, n, scale_log2);
+  else if (vec) hipLaunchKernelGGL(softmax_rows_reg_kernel<16>, dim3(rows), dim3(256), 0, s, sc, lds_, out, ldo, n, scale_log2);
+  else hipLaunchKernelGGL(softmax_rows_kernel, dim3(rows), dim3(256), 0, s, sc, lds_, out, ldo, n, scale_log2);
 }
 
 // out[(y*W + x)*C + c] (fp32, channels-last, C small) from the fp32 product rows: plain copy is

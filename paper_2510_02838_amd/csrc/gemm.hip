@@ -105,7 +105,9 @@ __device__ __forceinline__ void tile_coords(const GemmProblem& P, int t, int& tm
 // the s-th share of the k-slabs and leaves its fp32 accumulators, in register order, in chunk
 // b of batch.partial for splitk_reduce_kernel (small-M problems have too few tiles to fill
 // the chip and a lone tile's k-loop runs at global-memory latency per slab).
-template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE>
+// CONV: every problem of the batch is a 3x3 convolution (GemmProblem::conv_w > 0); a separate
+// instantiation so that the plain product's address arithmetic stays as it is.
+template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE, bool CONV = false>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batch) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -146,7 +148,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   for (int i = 0; i < LA; ++i) {
     int q = i * NT + tid, r = q / CPR, pc = q % CPR, c = pc ^ swz_key<BKT>(r);
     int m = m0 + r; if (m >= P.M) m = P.M - 1;            // clamp: rows past M are never stored
-    if (P.conv_w > 0) {      // top-left pixel of the 3x3 window in the bordered image
+    if constexpr (CONV) {    // top-left pixel of the 3x3 window in the bordered image
       const int y = m / P.conv_w, x = m - y * P.conv_w;
       ga[i] = (uint32_t)(y * (P.conv_w + 2) + x) * (uint32_t)P.conv_cin + c * 8;
     } else {
@@ -188,7 +190,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     unsigned char* dA = smem + (kt % NS) * STAGE;
     const int ks = (kt < nk ? kt : nk - 1) * BKT;
     int ka = ks;             // A-side offset of the slab
-    if (P.conv_w > 0) {      // slab = 64 channels of one tap (ky, kx): shift by ky rows and kx pixels
+    if constexpr (CONV) {    // slab = 64 channels of one tap (ky, kx): shift by ky rows and kx pixels
       const int tap = ks / P.conv_cin, c0 = ks - tap * P.conv_cin, ky = tap / 3, kx = tap - 3 * ky;
       ka = (ky * (P.conv_w + 2) + kx) * P.conv_cin + c0;
     }
@@ -498,7 +500,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmBatch batc
   }
 }
 
-template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE = 0>
+template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE = 0, bool CONV = false>
 static void launch_t(hipStream_t s, GemmBatch& b) {
   int total = 0;
   for (int i = 0; i < b.n; ++i) {
@@ -511,7 +513,7 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
   b.total_tiles = total;
   if (total == 0) return;
   size_t lds = (size_t)NS * (BM + BN) * BKT * 2;
-  auto kern = gemm_kernel<BM, BN, WM, WN, BKT, NS, MODE>;
+  auto kern = gemm_kernel<BM, BN, WM, WN, BKT, NS, MODE, CONV>;
   static bool attr_done = false;
   if (!attr_done) {
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -565,11 +567,26 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     }
   }
   if (!tile) {
+    int max_n = 0;
+    for (int i = 0; i < b.n; ++i)
+      if (b.p[i].M > 0 && b.p[i].N > max_n) max_n = b.p[i].N;
+    if (max_n <= 128) tile = 128128;       // half or more of a 256-wide tile would be padding
+  }
+  if (!tile) {
     long long t256 = 0;
     for (int i = 0; i < b.n; ++i)
       t256 += (long long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
     const long long rem = t256 % 256;
     tile = (t256 >= 1024 || (t256 >= 256 && (rem == 0 || rem >= 64))) ? 1256256 : 128128;
+  }
+  bool conv = false, plain = false;
+  for (int i = 0; i < b.n; ++i) { conv = conv || b.p[i].conv_w > 0; plain = plain || b.p[i].conv_w <= 0; }
+  if (conv) {     // convolutions: never mixed with plain products, three tile shapes
+    if (plain) return -1;
+    if (tile == 1256256) launch_t<256, 256, 2, 4, 64, 2, 0, true>(s, b);
+    else if (tile == 30128128) launch_t<128, 128, 2, 2, 64, 4, 0, true>(s, b);
+    else { tile = 128128; launch_t<128, 128, 2, 2, 64, 2, 0, true>(s, b); }
+    return tile;
   }
   switch (tile) {
     case 256256: launch_t<256, 256, 2, 2, 64, 2>(s, b); break;

@@ -1,7 +1,8 @@
 #!/usr/bin/env python3
 """Offline profiler of the Diffuse stage on one MI355X (k = 1, no sequence parallelism).
 
-Two tables, both measured through the library's dit_sample on seeded synthetic requests:
+Two tables measured through the library's dit_sample on seeded synthetic requests, and one
+each for the stages before and after it:
 
   batch   same-shape dynamic batching (Appendix "Impact of Batch Size" / "Integration with
           Dynamic Batch"): step latency against batch size B per request shape, and the
@@ -18,7 +19,12 @@ Two tables, both measured through the library's dit_sample on seeded synthetic r
 
     python -m paper_2510_02838_amd.stage_profile batch [--workload sd3] [--res 128,256,512] [--max-batch 32]
     python -m paper_2510_02838_amd.stage_profile grid  [--workload sd3|flux|wan] [--res ...]
+  decode  the Decode stage (AutoencoderKL-style decoder): latency, product flop rate and the
+          bytes held per image resolution (the paper: Encode and Decode are memory-bound and can
+          reach a higher peak memory than Diffuse).
+
     python -m paper_2510_02838_amd.stage_profile encode [--encoder t5_xxl] [--lens 32,128,500] [--max-batch 64]
+    python -m paper_2510_02838_amd.stage_profile decode [--decoder ae_kl] [--res 256,512,1024]
 
 Resolutions are pixels; a latent is res/8 on a side and a patch 2x2, so tokens = (res/16)^2
 plus the text tokens of the workload.  For the video family `--res` lists
@@ -202,6 +208,59 @@ def run_encode(args):
         print(f"| {n} | {cells} | {optimal_batch(lat)} |", file=sys.stderr)
 
 
+def decoder_flops(arch, h, w):
+    """Multiply-add flops (2 per MAC) of the products of one decode of an h x w latent."""
+    ch = arch["channels"]
+    conv = lambda px, cin, cout, k: 2.0 * px * k * k * cin * cout
+    res = lambda px, cin, cout: conv(px, cin, cout, 3) + conv(px, cout, cout, 3) + (conv(px, cin, cout, 1) if cin != cout else 0.0)
+    px = h * w
+    total = conv(px, arch["latent_ch"], ch[0], 3) + 2 * res(px, ch[0], ch[0])
+    total += 4 * conv(px, ch[0], ch[0], 1) + 4.0 * px * px * ch[0]          # q, k, v, proj; scores and weighted sum
+    prev = ch[0]
+    for l, c in enumerate(ch):
+        for r in range(arch["n_res"]):
+            total += res(px, prev if r == 0 else c, c)
+        prev = c
+        if l != len(ch) - 1:
+            px *= 4
+            total += conv(px, c, c, 3)
+    return total + conv(px, ch[-1], arch["out_ch"], 3)
+
+
+def run_decode(args):
+    import torch
+    import synth
+    from . import decoder as X
+    arch = synth.DECODERS[args.decoder]
+    m = X.Decoder(arch)
+    f = m.up_factor()
+    sizes = [int(v) // f for v in args.res.split(",")]
+    m.ensure_workspace(max(sizes), max(sizes))
+    m.init_weights(1, 0.02)
+    print("| image | latent | ms | product TFLOP/s | GFLOP | workspace GiB | weights MiB |", file=sys.stderr)
+    print("|---|---|---|---|---|---|---|", file=sys.stderr)
+    for n in sizes:
+        z = torch.from_numpy(synth.gaussian(3, "latent", arch["latent_ch"] * n * n).astype(np.float32)).cuda()
+        img = torch.empty((n * f, n * f, arch["out_ch"]), dtype=torch.float32, device="cuda")
+        m.forward(n, n, z, img)
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(3):
+            t0 = time.perf_counter()
+            m.forward(n, n, z, img)
+            torch.cuda.synchronize()
+            best = min(best, time.perf_counter() - t0)
+        if not bool(torch.isfinite(img).all().item()):
+            raise RuntimeError("non-finite image")
+        fl = decoder_flops(arch, n, n)
+        ws = m.workspace_bytes(n, n)
+        row = {"table": "decode", "decoder": args.decoder, "image": n * f, "latent": n, "ms": best * 1e3,
+               "product_flops": fl, "tflops": fl / best / 1e12, "workspace_bytes": ws, "weight_bytes": m.weight_bytes()}
+        print(json.dumps(row), flush=True)
+        print(f"| {n * f}x{n * f} | {n}x{n} | {best * 1e3:.2f} | {fl / best / 1e12:.0f} | {fl / 1e9:.0f} | {ws / 2**30:.2f} | "
+              f"{m.weight_bytes() / 2**20:.0f} |", file=sys.stderr)
+
+
 DEFAULT_RES = {
     ("batch", "sd3"): "128,256,512",
     ("batch", "flux"): "128,256,512",
@@ -213,7 +272,8 @@ DEFAULT_RES = {
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("table", choices=["batch", "grid", "encode"])
+    ap.add_argument("table", choices=["batch", "grid", "encode", "decode"])
+    ap.add_argument("--decoder", default="ae_kl", choices=["ae_kl", "ae_tiny"])
     ap.add_argument("--encoder", default="t5_xxl", choices=["t5_xxl", "t5_tiny"])
     ap.add_argument("--lens", default="32,128,500")
     ap.add_argument("--workload", default="sd3", choices=["sd3", "flux", "wan", "tiny"])
@@ -225,6 +285,9 @@ def main():
         args.max_batch = 64 if args.table == "encode" else 32
     if args.table == "encode":
         return run_encode(args)
+    if args.table == "decode":
+        args.res = args.res or "256,512,1024"
+        return run_decode(args)
     if args.res is None:
         args.res = DEFAULT_RES.get((args.table, args.workload))
         if args.res is None:

@@ -190,6 +190,24 @@ def test_decoder_wide_configuration_against_oracle(torch, X):
 
 
 @pytest.mark.gpu
+def test_decoder_mid_attention_over_thousands_of_pixels(torch, X):
+    """5184 latent pixels: the score and weighted-sum products span many tiles with a ragged last
+    one, and the softmax rows take the wide register-resident path (more than 4096 columns)."""
+    arch = dict(latent_ch=16, out_ch=3, channels=(128, 64), n_res=1)
+    params = _params(arch, seed=4)
+    z = _latent(arch, 72, 72)
+    m, got, taps = _run(torch, X, arch, params, z, ["mid.res0", "mid.attn"])
+    ref_taps = {}
+    ref = D.DecoderOracle(arch, params).forward(np.transpose(z, (1, 2, 0)), ref_taps)
+    # the attention's own contribution, not the stream it is added to
+    d_got = taps["mid.attn"].astype(np.float64) - taps["mid.res0"]
+    d_ref = (ref_taps["mid.attn"] - ref_taps["mid.res0"]).reshape(d_got.shape)
+    assert rel_l2(d_got, d_ref) <= 1e-2, rel_l2(d_got, d_ref)
+    _check_image(got, ref)
+    m.close()
+
+
+@pytest.mark.gpu
 def test_decoder_smaller_call_after_a_larger_one_is_unaffected(torch, X):
     """The workspace is reused with other image sizes: zero borders and padded channels must not
     carry over.  Same context, large then small latent, against a fresh context."""
