@@ -179,10 +179,11 @@ def test_decoder_difference_is_storage_rounding(torch, X):
 @pytest.mark.gpu
 def test_decoder_wide_configuration_against_oracle(torch, X):
     """The full-width decoder (512..128 channels, three residual blocks per level, 1x1 shortcuts
-    where the width drops) on a latent small enough for the float64 reference."""
+    where the width drops) on a latent small enough for the float64 reference (192 x 192 image:
+    up to 36864 product rows, several tile shapes)."""
     arch = synth.DECODERS["ae_kl"]
     params = _params(arch, seed=2)
-    z = _latent(arch, 8, 8)
+    z = _latent(arch, 24, 24)
     m, got, _ = _run(torch, X, arch, params, z)
     ref = D.DecoderOracle(arch, params).forward(np.transpose(z, (1, 2, 0)))
     _check_image(got, ref)
@@ -243,6 +244,64 @@ def test_decoder_device_init_matches_host_generator(torch, X):
     torch.cuda.synchronize()
     ref = D.DecoderOracle(ARCH, host).forward(np.transpose(z, (1, 2, 0)))
     _check_image(img.cpu().numpy(), ref)
+    m.close()
+
+
+@pytest.mark.gpu
+def test_decoder_full_size_last_stage_on_sampled_pixels_and_flip_symmetry(torch, X):
+    """The benchmark shape (ae_kl, 128 x 128 latent, 1024 x 1024 image, a million product rows).
+    The float64 reference cannot run the whole network at this size, so: (1) from the library's
+    captured last stream the reference computes GroupNorm over the full tensor and the last
+    convolution at sampled pixels, corners and edges included; (2) a property that holds at any
+    size: mirroring the latent and every 3x3 kernel left-right mirrors the image (equal up to
+    the storage-rounding noise of the parity tests, since the summation order changes)."""
+    arch = synth.DECODERS["ae_kl"]
+    h = w = 128
+    m = X.Decoder(arch)
+    m.ensure_workspace(h, w)
+    m.init_weights(1, 0.02)
+    f = m.up_factor()
+    H, W, C = h * f, w * f, arch["channels"][-1]
+    z = _latent(arch, h, w)
+    top = torch.zeros((H * W, C), dtype=torch.float32, device="cuda")
+    m.set_tap("up3", top)
+    img = torch.full((H, W, 3), float("nan"), dtype=torch.float32, device="cuda")
+    m.forward(h, w, torch.from_numpy(z).cuda(), img)
+    torch.cuda.synchronize()
+    got = img.cpu().numpy()
+    assert np.isfinite(got).all()
+    m.clear_taps()
+    img2 = torch.empty_like(img)
+    m.forward(h, w, torch.from_numpy(z).cuda(), img2)
+    torch.cuda.synchronize()
+    assert torch.equal(img, img2)                                   # deterministic
+    # (1) last stage at sampled pixels
+    shapes = D.param_shapes(arch)
+    last = {n: m.get_tensor(n, shapes[n][0]).astype(np.float64) for n in ("out.gn.g", "out.gn.b", "conv_out.w", "conv_out.b")}
+    x = top.cpu().numpy().astype(np.float64).reshape(H, W, C)
+    del top
+    y = D.silu(D.group_norm(x, last["out.gn.g"], last["out.gn.b"]))
+    del x
+    yp = np.zeros((H + 2, W + 2, C))
+    yp[1:-1, 1:-1] = y
+    del y
+    rng = np.random.default_rng(0)
+    pix = [(0, 0), (0, W - 1), (H - 1, 0), (H - 1, W - 1), (0, 517), (H - 1, 300), (411, 0), (702, W - 1), (1, 1), (H - 2, W - 2)]
+    pix += [(int(a), int(b)) for a, b in zip(rng.integers(0, H, 300), rng.integers(0, W, 300))]
+    ref = np.stack([D.conv2d(yp[a:a + 3, b:b + 3], last["conv_out.w"], last["conv_out.b"], 3)[1, 1] for a, b in pix])
+    g = np.stack([got[a, b] for a, b in pix])
+    assert max_abs(g, ref) <= 1e-2 * np.abs(ref).max(), (max_abs(g, ref), np.abs(ref).max())
+    assert rel_l2(g, ref) <= 5e-3, rel_l2(g, ref)
+    # (2) mirror symmetry
+    for name, (shape, kind) in shapes.items():
+        if kind == "matrix" and shape[0] % 9 == 0 and not name.startswith("mid.attn.") and ".short" not in name:
+            wgt = m.get_tensor(name, shape).reshape(3, 3, shape[0] // 9, shape[1])
+            m.set_tensor(name, wgt[:, ::-1])
+    m.forward(h, w, torch.from_numpy(np.ascontiguousarray(z[:, :, ::-1])).cuda(), img2)
+    torch.cuda.synchronize()
+    mirrored = img2.cpu().numpy()[:, ::-1]
+    assert rel_l2(mirrored, got) <= 2e-2, rel_l2(mirrored, got)
+    assert max_abs(mirrored, got) <= 5e-2 * np.abs(got).max()
     m.close()
 
 
