@@ -158,8 +158,9 @@ void plan(const dec_ctx* c, int h, int w, Layout& L) {
   L.vt = take(rup(C0, 256) * rup(L.P0, 64) * 2);            // read as a second operand: rows up to a multiple of 256
   L.sc = take((size_t)L.P0 * L.P0 * 4);
   L.pm = take((size_t)L.P0 * rup(L.P0, 64) * 2);
-  L.gnp = take(group_norm_partial_bytes((long long)L.Hf * L.Wf, 1024));
-  L.gst = take(GROUPS * sizeof(float2));
+  // channel sums per chunk of 64 pixels at least (the smallest wave height of a product tile)
+  L.gnp = take(std::max(group_norm_partial_bytes((long long)L.Hf * L.Wf, 1024), max_x / 64 * 8 + 2 * 1024 * 8));
+  L.gst = take(GN_STATS_BYTES);
   L.out4 = take((size_t)L.Hf * L.Wf * 4 * 4);
   L.partial = take(PARTIAL_BYTES);
   L.total = o;
@@ -178,25 +179,37 @@ GemmProblem prob(const bf16_t* A, int lda, const bf16_t* W, int ldw, const float
 
 struct Fwd {
   dec_ctx* c; const Layout& L; unsigned char* ws; hipStream_t s;
+  // the buffer whose per-chunk channel sums the last convolution left in the group-norm scratch
+  mutable const float* stats_of = nullptr;
+  mutable int stats_chunks = 0;
   template <class T> T* at(size_t off) const { return (T*)(ws + off); }
-  void gemm(std::initializer_list<GemmProblem> ps) const {
+  int gemm(std::initializer_list<GemmProblem> ps) const {
     GemmBatch b;
     b.n = 0; b.total_tiles = 0;
-    for (const GemmProblem& p : ps) b.p[b.n++] = p;
+    for (const GemmProblem& p : ps) {
+      if (p.out == stats_of) stats_of = nullptr;      // the buffer changes: its sums are stale
+      b.p[b.n++] = p;
+    }
     b.partial = at<float>(L.partial); b.partial_bytes = PARTIAL_BYTES;
-    launch_gemm(s, b);
+    return launch_gemm(s, b);
   }
   // 3x3 convolution of the bordered bf16 image `img` (H x W, cin_pad channels) into fp32 rows
-  void conv3(const std::string& name, const bf16_t* img, int H, int W, int kind, float* out, int ldc) const {
+  void conv3(const std::string& name, const bf16_t* img, int H, int W, int kind, float* out, int ldc, bool sums = true) const {
     const DTensor* t = find(c, name + ".w");
     GemmProblem p = prob(img, t->cin_pad, Wm(c, name + ".w"), t->ld, Wv(c, name + ".b"), H * W, t->cols_out,
                          9 * t->cin_pad, kind, out, ldc);
     p.conv_w = W; p.conv_cin = t->cin_pad;
-    gemm({p});
+    const bool want = sums && (kind == OUT_F32 || kind == OUT_RESID_F32);   // a group norm reads `out` next
+    if (want) p.stats = at<float>(L.gnp);
+    const int tile = gemm({p});
+    if (want) {
+      const int rows = gemm_stats_rows(tile);
+      stats_of = out; stats_chunks = (H * W + 2 * rows - 1) / (2 * rows) * 2;
+    }
   }
   void gn(const std::string& name, const float* x, bf16_t* out, int H, int W, int C, int silu, int pad) const {
     launch_group_norm(s, x, Wv(c, name + ".g"), Wv(c, name + ".b"), out, at<float>(L.gnp), at<float2>(L.gst), H, W, C,
-                      GROUPS, silu, pad);
+                      GROUPS, silu, pad, x == stats_of ? stats_chunks : 0);
   }
   void zero_img(int H, int W, int C) const {       // the border must be zero; the interior is overwritten
     launch_zero_border(s, at<bf16_t>(L.img), H, W, C);
@@ -456,7 +469,7 @@ dit_status dec_forward(dec_ctx* c, int h, int w, const float* latent, float* ima
   // output: GN + SiLU + conv to out_ch channels (product rows are 4 wide, then compacted)
   F.zero_img(H, W, prev);
   F.gn("out.gn", x, img, H, W, prev, 1, 1);
-  F.conv3("conv_out", img, H, W, OUT_F32, F.at<float>(L.out4), 4);
+  F.conv3("conv_out", img, H, W, OUT_F32, F.at<float>(L.out4), 4, false);
   launch_compact_rows(s, F.at<float>(L.out4), 4, image, (long long)H * W, g.out_ch);
   DHIP(c, hipGetLastError());
   return DIT_OK;

@@ -102,14 +102,18 @@ __global__ __launch_bounds__(256) void gn_partial_kernel(const float* __restrict
     partial[((size_t)blockIdx.x * C + c) * 2 + 1] = b;
   }
 }
-// pass 2: one workgroup per group: chunks and the group's channels summed in fixed order (float64
-// accumulation of the chunk sums); stats[g] = (mean, 1/sqrt(var + eps))
+// pass 2: one workgroup per (group, share of the chunks): chunk sums of the group's channels added
+// in fixed order in float64.  With one share per group the workgroup writes stats[g] = (mean,
+// 1/sqrt(var + eps)) itself; with several it leaves (sum, sum of squares) in part[g][share] for
+// gn_combine_kernel (many chunks: 32 workgroups alone would take longer than the apply pass).
 __global__ __launch_bounds__(256) void gn_finalize_kernel(const float* __restrict__ partial, float2* __restrict__ stats,
-                                                          int chunks, int C, int groups, long long P) {
+                                                          double2* __restrict__ part, int chunks, int C, int groups, long long P) {
   __shared__ double rs[256], rq[256];
   const int g = blockIdx.x, cpg = C / groups, tid = threadIdx.x;
+  const int shares = gridDim.y, sh = blockIdx.y;
+  const int c0 = (int)((long long)chunks * sh / shares), c1 = (int)((long long)chunks * (sh + 1) / shares);
   double a = 0.0, b = 0.0;
-  for (int ch = tid; ch < chunks; ch += 256)
+  for (int ch = c0 + tid; ch < c1; ch += 256)
     for (int c = 0; c < cpg; ++c) {
       const float* pp = partial + ((size_t)ch * C + g * cpg + c) * 2;
       a += (double)pp[0]; b += (double)pp[1];
@@ -121,11 +125,23 @@ __global__ __launch_bounds__(256) void gn_finalize_kernel(const float* __restric
     __syncthreads();
   }
   if (tid == 0) {
+    if (shares > 1) { part[g * shares + sh] = make_double2(rs[0], rq[0]); return; }
     const double n = (double)P * cpg, mean = rs[0] / n;
     double var = rq[0] / n - mean * mean;
     if (var < 0.0) var = 0.0;
     stats[g] = make_float2((float)mean, (float)(1.0 / sqrt(var + 1e-6)));
   }
+}
+__global__ __launch_bounds__(64) void gn_combine_kernel(const double2* __restrict__ part, float2* __restrict__ stats,
+                                                        int shares, int cpg, int groups, long long P) {
+  const int g = threadIdx.x;
+  if (g >= groups) return;
+  double a = 0.0, b = 0.0;
+  for (int s = 0; s < shares; ++s) { a += part[g * shares + s].x; b += part[g * shares + s].y; }
+  const double n = (double)P * cpg, mean = a / n;
+  double var = b / n - mean * mean;
+  if (var < 0.0) var = 0.0;
+  stats[g] = make_float2((float)mean, (float)(1.0 / sqrt(var + 1e-6)));
 }
 // pass 3: y = (x - mean_g) rstd_g gamma_c + beta_c, optional SiLU, bf16, bordered or plain rows.
 // One image row per blockIdx.y; a thread takes 8 consecutive channels of one pixel.
@@ -155,18 +171,28 @@ __global__ __launch_bounds__(256) void gn_apply_kernel(const float* __restrict__
   *(uint4*)(out + dst_pixel(y, xx, W, pad) * C + c) = w;
 }
 
+// ready_chunks > 0: `partial` already holds the per-chunk channel sums of x (written by the
+// epilogue of the convolution that produced x, any chunk height): pass 1 is skipped.
 void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const float* beta, bf16_t* out,
-                       float* partial, float2* stats, int H, int W, int C, int groups, int silu, int pad) {
+                       float* partial, float2* stats, int H, int W, int C, int groups, int silu, int pad,
+                       int ready_chunks) {
   const long long P = (long long)H * W;
   if (P == 0) return;
-  const int chunks = (int)((P + GN_CHUNK - 1) / GN_CHUNK);
+  int chunks = ready_chunks;
   int csh = 0;
   while ((1 << csh) < C) ++csh;                  // C = 1 << csh
   int gsh = 0;
   while ((groups << gsh) < C) ++gsh;             // channels per group = 1 << gsh
-  const int pix_par = 256 >> (csh - 2);
-  hipLaunchKernelGGL(gn_partial_kernel, dim3(chunks), dim3(256), (size_t)pix_par * C * 2 * sizeof(float), s, x, partial, P, C, csh - 2);
-  hipLaunchKernelGGL(gn_finalize_kernel, dim3(groups), dim3(256), 0, s, partial, stats, chunks, C, groups, P);
+  if (chunks <= 0) {
+    chunks = (int)((P + GN_CHUNK - 1) / GN_CHUNK);
+    const int pix_par = 256 >> (csh - 2);
+    hipLaunchKernelGGL(gn_partial_kernel, dim3(chunks), dim3(256), (size_t)pix_par * C * 2 * sizeof(float), s, x, partial, P, C, csh - 2);
+  }
+  // stats: [groups] float2 followed (256 bytes on) by the [groups][shares] float64 pairs of the two-stage form
+  const int shares = chunks >= 4096 ? 16 : (chunks >= 1024 ? 4 : 1);
+  double2* part = (double2*)((unsigned char*)stats + 256);
+  hipLaunchKernelGGL(gn_finalize_kernel, dim3(groups, shares), dim3(256), 0, s, partial, stats, part, chunks, C, groups, P);
+  if (shares > 1) hipLaunchKernelGGL(gn_combine_kernel, dim3(1), dim3(64), 0, s, part, stats, shares, C / groups, groups, P);
   const int units = W * (C >> 3);
   hipLaunchKernelGGL(gn_apply_kernel, dim3((units + 255) / 256, H), dim3(256), 0, s, x, stats, gamma, beta, out, W, C, csh - 3, gsh, silu, pad);
 }

@@ -36,6 +36,10 @@ struct GemmProblem {
   // zero border, [(H+2)*(conv_w+2)][conv_cin]; row m of the product is output pixel (m / conv_w,
   // m % conv_w), column index k = tap*conv_cin + c with tap = 3*ky + kx; conv_cin % 64 == 0, K = 9*conv_cin.
   int conv_w = 0, conv_cin = 0;
+  // convolutions with OUT_F32 / OUT_RESID_F32 only, optional: per column n, the sum and the sum
+  // of squares of the stored values over the rows of each (tile row, wave row) pair:
+  // stats[(tile_row * 2 + wave_row)][N][2], rows of a pair = tile height / 2 (gemm_stats_rows)
+  float* stats = nullptr;
   int tiles_m, tiles_n, tile_start;                        // filled by the launcher
 };
 struct GemmBatch {
@@ -47,6 +51,7 @@ struct GemmBatch {
 
 // Launches up to 3 independent problems in one grid.  Returns the tile shape used (BM*1000+BN).
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile = 0);
+inline int gemm_stats_rows(int tile_code) { return (tile_code % 1000000) / 1000 / 2; }   // rows per stats chunk
 
 // ---- attention ----------------------------------------------------------------------
 struct AttnTile { int seg; int q0; };   // one block of q_per_tile queries of one segment
@@ -142,10 +147,13 @@ void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, i
 void launch_zero_border(hipStream_t s, bf16_t* img, int H, int W, int C);   // C % 8 == 0
 // GroupNorm (eps 1e-6, affine) of the fp32 stream x [H*W][C], optional SiLU, bf16 output with
 // (pad=1) or without a one-pixel border.  C in {64,128,256,512,1024}; partial: scratch of
-// group_norm_partial_bytes; stats: [groups] float2.
+// group_norm_partial_bytes; stats: scratch of GN_STATS_BYTES (groups <= 32).  ready_chunks > 0: partial already holds
+// [ready_chunks][C][2] channel sums of x (GemmProblem::stats) and the statistics pass is skipped.
 size_t group_norm_partial_bytes(long long pixels, int C);
+constexpr size_t GN_STATS_BYTES = 256 + 32 * 16 * 16;
 void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const float* beta, bf16_t* out,
-                       float* partial, float2* stats, int H, int W, int C, int groups, int silu, int pad);
+                       float* partial, float2* stats, int H, int W, int C, int groups, int silu, int pad,
+                       int ready_chunks = 0);
 // nearest 2x upsampling of x [H*W][C] fp32 into a bf16 bordered image of size 2H x 2W
 void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C);
 void launch_cast_bf16(hipStream_t s, const float* x, bf16_t* out, long long n);     // n % 4 == 0

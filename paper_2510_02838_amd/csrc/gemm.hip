@@ -299,6 +299,14 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     float bv[VEC];
 #pragma unroll
     for (int c = 0; c < VEC; ++c) bv[c] = (P.bias && n + c < P.N) ? P.bias[n + c] : 0.f;
+    // convolutions with fp32 output: per-column sums and sums of squares of the values stored,
+    // over this wave's rows (the statistics pass of the group norm that follows)
+    constexpr bool STATS = CONV && F32OUT;
+    float cs[STATS ? VEC : 1], cq[STATS ? VEC : 1];
+    if constexpr (STATS) {
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) { cs[c] = 0.f; cq[c] = 0.f; }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -330,8 +338,16 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 #pragma unroll
             for (int c = 0; c < 4; ++c) x4[c] += g4[c] * v[c];
             *(f32x4*)xp = x4;
+            if constexpr (STATS) {
+#pragma unroll
+              for (int c = 0; c < 4; ++c) { cs[c] += x4[c]; cq[c] += x4[c] * x4[c]; }
+            }
           } else {
-            for (int c = 0; c < VEC && n + c < P.N; ++c) xp[c] += (gp ? gp[c] : 1.f) * v[c];
+            for (int c = 0; c < VEC && n + c < P.N; ++c) {
+              const float r = xp[c] + (gp ? gp[c] : 1.f) * v[c];
+              xp[c] = r;
+              if constexpr (STATS) { cs[c] += r; cq[c] += r * r; }
+            }
           }
         } else if constexpr (KIND == OUT_F32) {
           float* xp = (float*)P.out + o;
@@ -340,6 +356,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
             *(f32x4*)xp = x4;
           } else {
             for (int c = 0; c < VEC && n + c < P.N; ++c) xp[c] = v[c];
+          }
+          if constexpr (STATS) {
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) { cs[c] += v[c]; cq[c] += v[c] * v[c]; }   // (columns past N are not written out)
           }
         } else {
           if constexpr (KIND == OUT_GELU_BF16) {
@@ -358,6 +378,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
         }
       }
       asm volatile("" ::: "memory");
+    }
+    if constexpr (STATS) {
+      if (P.stats) {      // partial[(tile row * WM + wm)][column][2]: rows of one wave of one tile
+#pragma unroll
+        for (int c = 0; c < VEC; ++c)
+#pragma unroll
+          for (int o = LPR; o < 64; o <<= 1) { cs[c] += __shfl_xor(cs[c], o); cq[c] += __shfl_xor(cq[c], o); }
+        if (lr == 0) {
+          float* sp = P.stats + ((size_t)(tm * WM + wm) * P.N + n) * 2;
+          for (int c = 0; c < VEC && n + c < P.N; ++c) { sp[2 * c] = cs[c]; sp[2 * c + 1] = cq[c]; }
+        }
+      }
     }
   };
   // q/k columns of a QKV product: RMS norm per head, gain, rotary code, scale, scatter by row.
