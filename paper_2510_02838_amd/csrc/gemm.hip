@@ -563,7 +563,9 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
 //   +1000000  8 waves (2x4) instead of 4 (2x2)
 //   +10000000 k-slab 32 with a 4-stage ring, +20000000 k-slab 32 with a 5-stage ring
 //             (default: k-slab 64, 2 stages)
-//   6256256 / 7256256  measurement probes on the 8-wave 256x256 k-slab-64 kernel
+//   6256256 / 7256256  measurement probes on the 8-wave 256x256 k-slab-64 kernel,
+//   8256256 / 9256256  the same on the 4-wave one
+//   31256128 / 32256128 / 31128256  256x128 (4 waves / 8 waves) and 128x256 with a 3-stage ring
 //   30128128  128x128, k-slab 64, 4-stage ring (one workgroup per CU: for grids below 256 tiles)
 //   40128128  the same as split-K over b.splits shares of K plus the reduction kernel
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
@@ -599,6 +601,20 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     }
   }
   if (!tile) {
+    // One round of 256x128 tiles (8 waves, 3-stage ring) when that fits the chip and K is long:
+    // a workgroup per CU with three slabs in flight, against 1.6 128x128 workgroups per CU.
+    long long t21 = 0;
+    int min_k = 1 << 30;
+    bool plain = true;
+    for (int i = 0; i < b.n; ++i) {
+      if (b.p[i].M <= 0 || b.p[i].N <= 0) continue;
+      t21 += (long long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 127) / 128);
+      min_k = b.p[i].K < min_k ? b.p[i].K : min_k;
+      plain = plain && b.p[i].out_kind != OUT_QKNORM && b.p[i].conv_w <= 0;
+    }
+    if (plain && t21 > 128 && t21 <= 256 && min_k >= 4096) tile = 32256128;
+  }
+  if (!tile) {
     int max_n = 0;
     for (int i = 0; i < b.n; ++i)
       if (b.p[i].M > 0 && b.p[i].N > max_n) max_n = b.p[i].N;
@@ -629,10 +645,15 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     case 21256256: launch_t<256, 256, 2, 4, 32, 5>(s, b); break;
     case 6256256: launch_t<256, 256, 2, 4, 64, 2, 2>(s, b); break;
     case 7256256: launch_t<256, 256, 2, 4, 64, 2, 3>(s, b); break;
+    case 8256256: launch_t<256, 256, 2, 2, 64, 2, 2>(s, b); break;
+    case 9256256: launch_t<256, 256, 2, 2, 64, 2, 3>(s, b); break;
     case 256128: launch_t<256, 128, 2, 2, 64, 2>(s, b); break;
     case 128256: launch_t<128, 256, 2, 2, 64, 2>(s, b); break;
     case 10128128: launch_t<128, 128, 2, 2, 32, 4>(s, b); break;
     case 30128128: launch_t<128, 128, 2, 2, 64, 4>(s, b); break;
+    case 31256128: launch_t<256, 128, 2, 2, 64, 3>(s, b); break;
+    case 32256128: launch_t<256, 128, 4, 2, 64, 3>(s, b); break;
+    case 31128256: launch_t<128, 256, 2, 2, 64, 3>(s, b); break;
     case 40128128: launch_t<128, 128, 2, 2, 64, 4, 4>(s, b); break;
     default: tile = 128128; launch_t<128, 128, 2, 2, 64, 2>(s, b); break;
   }
