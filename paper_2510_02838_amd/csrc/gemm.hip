@@ -73,6 +73,16 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 // scheduling hint for one k-step: NR LDS reads spread over NM MFMAs
 template <int NR, int NM>
 __device__ __forceinline__ void interleave_hint() {
+  if constexpr (NM >= 16) {
+    // one wave per SIMD: nothing else covers LDS latency, so all reads go out in the first half
+#pragma unroll
+    for (int i = 0; i < NR; ++i) {
+      SGB(0x100, 1);
+      SGB(0x008, 1);
+    }
+    SGB(0x008, NM - NR);
+    return;
+  }
   constexpr int per = NM / NR, extra = NM - per * NR;
 #pragma unroll
   for (int i = 0; i < NR; ++i) {
