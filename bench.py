@@ -23,7 +23,7 @@ PEAK_HBM_GBS = 8000.0
 # Fabric-side bytes per GEMM launch (rocprofv3 FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, the scale
 # factors from the streaming calibration kernel), averaged over the GEMM launches of a step;
 # measured once per workload, see profiles/<workload>_hbm_traffic.txt.  None = not measured.
-MEASURED_GEMM_TRAFFIC_BYTES = {"sd3": 209.5e6}
+MEASURED_GEMM_TRAFFIC_BYTES = {"sd3": 219.3e6}
 
 
 def cpu_baseline(name, arch, reqs):

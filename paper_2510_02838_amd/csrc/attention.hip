@@ -321,11 +321,9 @@ template <int DH, int NW, int MODE>
 static void launch_t(hipStream_t s, const AttnArgs& a) {
   constexpr int lds = 2 * (KT * DH * 2 + DH * 128);   // two K tiles + two V^T tiles
   auto kern = attn_kernel<DH, NW, MODE>;
-  static bool done = false;
-  if (!done) {
+  static std::atomic<unsigned> seen{0};
+  if (first_use_on_device(seen))
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    done = true;
-  }
   hipLaunchKernelGGL(kern, dim3(a.n_tiles * a.n_heads), dim3(NW * 64), lds, s, a);
 }
 

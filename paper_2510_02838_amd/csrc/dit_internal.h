@@ -3,10 +3,20 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
 
 namespace dit {
 
 typedef uint16_t bf16_t;  // storage type of bf16 tensors
+
+// A kernel's dynamic-LDS limit is a per-device attribute: true the first time the calling thread's
+// current device is seen for `mask` (one mask per kernel instantiation; devices 0..31).
+inline bool first_use_on_device(std::atomic<unsigned>& mask) {
+  int dev = 0;
+  (void)hipGetDevice(&dev);
+  const unsigned bit = 1u << (dev & 31);
+  return (mask.fetch_or(bit) & bit) == 0;
+}
 
 // ---- GEMM ---------------------------------------------------------------------------
 enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_GELU_BF16 = 2, OUT_RESID_F32 = 3, OUT_QKNORM = 4 };

@@ -556,11 +556,9 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
   if (total == 0) return;
   size_t lds = (size_t)NS * (BM + BN) * BKT * 2;
   auto kern = gemm_kernel<BM, BN, WM, WN, BKT, NS, MODE, CONV>;
-  static bool attr_done = false;
-  if (!attr_done) {
+  static std::atomic<unsigned> seen{0};
+  if (first_use_on_device(seen))
     (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    attr_done = true;
-  }
   if (MODE == 4) {
     hipLaunchKernelGGL(kern, dim3(total * b.splits), dim3(WM * WN * 64), lds, s, b);
     hipLaunchKernelGGL((splitk_reduce_kernel<BM, BN, WM, WN>), dim3(total * (BM * BN / 1024)), dim3(256), 0, s, b);
