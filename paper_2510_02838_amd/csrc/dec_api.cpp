@@ -469,8 +469,13 @@ dit_status dec_forward(dec_ctx* c, int h, int w, const float* latent, float* ima
   // output: GN + SiLU + conv to out_ch channels (product rows are 4 wide, then compacted)
   F.zero_img(H, W, prev);
   F.gn("out.gn", x, img, H, W, prev, 1, 1);
-  F.conv3("conv_out", img, H, W, OUT_F32, F.at<float>(L.out4), 4, false);
-  launch_compact_rows(s, F.at<float>(L.out4), 4, image, (long long)H * W, g.out_ch);
+  {
+    const DTensor* to = find(c, "conv_out.w");
+    if (!launch_conv3_small(s, img, Wm(c, "conv_out.w"), to->ld, Wv(c, "conv_out.b"), image, H, W, to->cin_pad, g.out_ch)) {
+      F.conv3("conv_out", img, H, W, OUT_F32, F.at<float>(L.out4), 4, false);     // wide last level: as a product
+      launch_compact_rows(s, F.at<float>(L.out4), 4, image, (long long)H * W, g.out_ch);
+    }
+  }
   DHIP(c, hipGetLastError());
   return DIT_OK;
 }

@@ -308,6 +308,79 @@ void launch_softmax_rows(hipStream_t s, const float* sc, int lds_, bf16_t* out, 
   else hipLaunchKernelGGL(softmax_rows_kernel, dim3(rows), dim3(256), 0, s, sc, lds_, out, ldo, n, scale_log2);
 }
 
+// 3x3 convolution to a few output channels (the decoder's last layer: 3), read-bound: a product
+// on the matrix cores would compute 128-column tiles for 3 columns.  C/8 lanes share a pixel, a
+// lane owns 8 channels: its 9 x OC weight pieces stay in registers while the wave walks over
+// pixels (coalesced 16-byte loads of whole pixel rows), bf16 pair dot products accumulate in
+// fp32 and the lanes of a pixel are summed by shuffles.  img: bordered bf16 image
+// [(H+2)(W+2)][C]; w: bf16 [>= OC][ldw], input index (3 ky + kx) C + c; out: fp32 [H W][OC].
+// C in {64, 128, 256, 512}.
+template <int OC>
+__global__ __launch_bounds__(256) void conv3_small_kernel(const bf16_t* __restrict__ img, const bf16_t* __restrict__ w, int ldw,
+                                                          const float* __restrict__ bias, float* __restrict__ out,
+                                                          int H, int W, int C, int lsh) {
+  typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
+  const int lane = threadIdx.x & 63;
+  const int lpp = 1 << lsh;                         // lanes per pixel = C / 8
+  const int sub = lane & (lpp - 1), pl = lane >> lsh, ppw = 64 >> lsh;
+  uint4 wr[9][OC];
+#pragma unroll
+  for (int tap = 0; tap < 9; ++tap)
+#pragma unroll
+    for (int o = 0; o < OC; ++o) wr[tap][o] = *(const uint4*)(w + (size_t)o * ldw + tap * C + sub * 8);
+  const long long P = (long long)H * W;
+  const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6), nwaves = (long long)gridDim.x * 4;
+  for (long long p0 = wave * ppw; p0 < P; p0 += nwaves * ppw) {
+    const long long p = p0 + pl;
+    const bool ok = p < P;
+    const long long pc = ok ? p : P - 1;
+    const int y = (int)(pc / W), x = (int)(pc % W);
+    float acc[OC];
+#pragma unroll
+    for (int o = 0; o < OC; ++o) acc[o] = 0.f;
+    uint4 v[9];
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap)
+      v[tap] = *(const uint4*)(img + ((size_t)(y + tap / 3) * (W + 2) + (x + tap % 3)) * C + sub * 8);
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const uint32_t vv[4] = {v[tap].x, v[tap].y, v[tap].z, v[tap].w};
+#pragma unroll
+      for (int o = 0; o < OC; ++o) {
+        const uint32_t wv[4] = {wr[tap][o].x, wr[tap][o].y, wr[tap][o].z, wr[tap][o].w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+          acc[o] = __builtin_amdgcn_fdot2_f32_bf16(*(const bf2*)&vv[q], *(const bf2*)&wv[q], acc[o], false);
+      }
+    }
+    for (int off = 1; off < lpp; off <<= 1)
+#pragma unroll
+      for (int o = 0; o < OC; ++o) acc[o] += __shfl_xor(acc[o], off);
+    if (ok && sub == 0) {
+#pragma unroll
+      for (int o = 0; o < OC; ++o) out[p * OC + o] = acc[o] + (bias ? bias[o] : 0.f);
+    }
+  }
+}
+bool launch_conv3_small(hipStream_t s, const bf16_t* img, const bf16_t* w, int ldw, const float* bias, float* out,
+                        int H, int W, int C, int OC) {
+  if (OC < 1 || OC > 4 || (C != 64 && C != 128 && C != 256 && C != 512)) return false;
+  const long long P = (long long)H * W;
+  if (P == 0) return true;
+  int lsh = 0;
+  while ((8 << lsh) < C) ++lsh;
+  const long long groups = (P + (64 >> lsh) - 1) / (64 >> lsh);       // wave-loads of pixels
+  const long long want = (groups + 3) / 4;
+  dim3 g((unsigned)(want < 4096 ? want : 4096)), b(256);
+  switch (OC) {
+    case 1: hipLaunchKernelGGL(conv3_small_kernel<1>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh); break;
+    case 2: hipLaunchKernelGGL(conv3_small_kernel<2>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh); break;
+    case 3: hipLaunchKernelGGL(conv3_small_kernel<3>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh); break;
+    default: hipLaunchKernelGGL(conv3_small_kernel<4>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh); break;
+  }
+  return true;
+}
+
 // out[(y*W + x)*C + c] (fp32, channels-last, C small) from the fp32 product rows: plain copy is
 // not needed; the last convolution writes fp32 rows [pixels][ldc] and this kernel compacts them
 __global__ __launch_bounds__(256) void compact_rows_kernel(const float* __restrict__ src, int lds_, float* __restrict__ dst,

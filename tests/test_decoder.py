@@ -209,6 +209,20 @@ def test_decoder_mid_attention_over_thousands_of_pixels(torch, X):
 
 
 @pytest.mark.gpu
+def test_decoder_last_layer_as_a_product_when_the_last_level_is_wide(torch, X):
+    """With 1024 channels at the last level the 3-channel convolution is outside its direct
+    kernel's range (at most 64 lanes x 8 channels per pixel) and runs as a matrix product
+    instead; 4 latent channels."""
+    arch = dict(latent_ch=4, out_ch=3, channels=(128, 1024), n_res=1)
+    params = _params(arch, seed=6)
+    z = _latent(arch, 8, 8)
+    m, got, _ = _run(torch, X, arch, params, z)
+    ref = D.DecoderOracle(arch, params).forward(np.transpose(z, (1, 2, 0)))
+    _check_image(got, ref)
+    m.close()
+
+
+@pytest.mark.gpu
 def test_decoder_smaller_call_after_a_larger_one_is_unaffected(torch, X):
     """The workspace is reused with other image sizes: zero borders and padded channels must not
     carry over.  Same context, large then small latent, against a fresh context."""
