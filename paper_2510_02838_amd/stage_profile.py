@@ -25,6 +25,11 @@ each for the stages before and after it:
 
     python -m paper_2510_02838_amd.stage_profile encode [--encoder t5_xxl] [--lens 32,128,500] [--max-batch 64]
     python -m paper_2510_02838_amd.stage_profile decode [--decoder ae_kl] [--res 256,512,1024]
+    python -m paper_2510_02838_amd.stage_profile pipeline [--workload sd3|flux] [--res 512,1024] [--steps 28]
+
+  pipeline  one request through all three stages on this GPU, the output of each feeding the next
+          (prompt tokens -> condition -> T denoising steps -> image): time per stage and its share
+          of the request (the paper's stage-time breakdown: Diffuse dominates, Decode 15-30 %).
 
 Resolutions are pixels; a latent is res/8 on a side and a patch 2x2, so tokens = (res/16)^2
 plus the text tokens of the workload.  For the video family `--res` lists
@@ -261,6 +266,69 @@ def run_decode(args):
               f"{m.weight_bytes() / 2**20:.0f} |", file=sys.stderr)
 
 
+def run_pipeline(args):
+    import torch
+    import synth
+    from . import encoder as XE, decoder as XD
+    st = Stage(args.workload, args.steps)
+    arch = st.arch
+    enc_arch, dec_arch = synth.ENCODERS["t5_xxl"], synth.DECODERS["ae_kl"]
+    if arch["cond_dim"] != enc_arch["d_model"] or arch["latent_ch"] != dec_arch["latent_ch"] or arch["patch"][0] != 1:
+        raise SystemExit("pipeline: the workload's condition width / latent channels do not match t5_xxl / ae_kl")
+    specs = args.res.split(",")
+    reqs = [[_latent_dims(st.cfg, r) + (st.n_cond,)] for r in specs]
+    st.prepare(reqs)
+    enc = XE.Encoder(enc_arch)
+    lens = [st.n_cond]
+    enc.ensure_workspace(lens)
+    enc.init_weights(1, 0.02)
+    dec = XD.Decoder(dec_arch)
+    hmax = max(r[0][1] for r in reqs)
+    dec.ensure_workspace(hmax, hmax)
+    dec.init_weights(1, 0.02)
+    f = dec.up_factor()
+    toks = torch.from_numpy(np.concatenate(synth.make_tokens(lens, enc_arch["vocab"]))).cuda()
+    cond = torch.empty((st.n_cond, arch["cond_dim"]), dtype=torch.bfloat16, device="cuda")
+    sg = np.stack([synth.default_sigmas(args.steps, 1.0)])
+
+    def timed(fn, reps=3):
+        fn()
+        torch.cuda.synchronize()
+        best = float("inf")
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            fn()
+            torch.cuda.synchronize()
+            best = min(best, time.perf_counter() - t0)
+        return best
+
+    print(f"| image | tokens | encode ms | diffuse ms ({args.steps} steps) | decode ms | total ms | shares E / D / C |", file=sys.stderr)
+    print("|---|---|---|---|---|---|---|", file=sys.stderr)
+    for spec, rq in zip(specs, reqs):
+        _, h, w, _ = rq[0]
+        n = arch["latent_ch"] * h * w
+        x0 = torch.from_numpy(synth.gaussian(2, "latent", n).astype(np.float32)).cuda()
+        x = x0.clone()
+        img = torch.empty((h * f, w * f, dec_arch["out_ch"]), dtype=torch.float32, device="cuda")
+        st.m.ensure_workspace(rq, args.steps)
+        t_e = timed(lambda: enc.forward(lens, toks, cond, None))
+
+        def diffuse():
+            x.copy_(x0)
+            st.m.sample(rq, x, cond, sg)
+        t_d = timed(diffuse)
+        t_c = timed(lambda: dec.forward(h, w, x, img))
+        if not bool(torch.isfinite(img).all().item()):
+            raise RuntimeError("non-finite image")
+        tot = t_e + t_d + t_c
+        row = {"table": "pipeline", "workload": args.workload, "image": spec, "tokens": _tokens(arch, rq[0]),
+               "steps": args.steps, "encode_ms": t_e * 1e3, "diffuse_ms": t_d * 1e3, "decode_ms": t_c * 1e3,
+               "share_encode": t_e / tot, "share_diffuse": t_d / tot, "share_decode": t_c / tot}
+        print(json.dumps(row), flush=True)
+        print(f"| {spec} | {row['tokens']} | {t_e * 1e3:.2f} | {t_d * 1e3:.1f} | {t_c * 1e3:.2f} | {tot * 1e3:.1f} | "
+              f"{100 * t_e / tot:.1f} % / {100 * t_d / tot:.1f} % / {100 * t_c / tot:.1f} % |", file=sys.stderr)
+
+
 DEFAULT_RES = {
     ("batch", "sd3"): "128,256,512",
     ("batch", "flux"): "128,256,512",
@@ -272,7 +340,7 @@ DEFAULT_RES = {
 
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("table", choices=["batch", "grid", "encode", "decode"])
+    ap.add_argument("table", choices=["batch", "grid", "encode", "decode", "pipeline"])
     ap.add_argument("--decoder", default="ae_kl", choices=["ae_kl", "ae_tiny"])
     ap.add_argument("--encoder", default="t5_xxl", choices=["t5_xxl", "t5_tiny"])
     ap.add_argument("--lens", default="32,128,500")
@@ -288,6 +356,10 @@ def main():
     if args.table == "decode":
         args.res = args.res or "256,512,1024"
         return run_decode(args)
+    if args.table == "pipeline":
+        args.res = args.res or "512,1024"
+        args.steps = args.steps or 28
+        return run_pipeline(args)
     if args.res is None:
         args.res = DEFAULT_RES.get((args.table, args.workload))
         if args.res is None:
