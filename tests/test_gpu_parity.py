@@ -98,6 +98,36 @@ def test_gemm_against_float64_matmul(torch, B, M, N, K, variant):
         assert err.max() <= tol, (kind, err.max())
 
 
+def test_gemm_seeded_random_shapes(torch, B):
+    """Forty seeded shapes (M 1..900, N 1..900, K a multiple of 64 up to 2048), each with a seeded
+    output kind, through the launcher's own tile choice: ragged tiles in both directions, the
+    small-M path with and without split-K, the 128- and 256-wide tiles."""
+    rng = np.random.default_rng(12345)
+    for case in range(40):
+        M, N = int(rng.integers(1, 901)), int(rng.integers(1, 901))
+        K = 64 * int(rng.integers(1, 33))
+        kind = int(rng.integers(0, 3))
+        A = rnd(10 + case, "A", (M, K))
+        W = rnd(60 + case, "W", (N, K), 0.05)
+        bias = rnd(110 + case, "b", (N,), 0.5)
+        npad = (N + 255) // 256 * 256
+        Wp = np.zeros((npad, K), np.float32); Wp[:N] = W
+        dA, dW, dB = to_dev_bf16(torch, A), to_dev_bf16(torch, Wp), torch.from_numpy(bias).cuda()
+        ldc = (N + 7) // 8 * 8                       # row stride: a multiple of 16 bytes
+        out = torch.full((M, ldc), float("nan"), dtype=torch.float32 if kind == 1 else torch.bfloat16, device="cuda")
+        st = B.dit_op_gemm(None, dA.data_ptr(), K, dW.data_ptr(), K, dB.data_ptr(), M, N, K, kind, out.data_ptr(), ldc, None, 0, None)
+        assert st == 0, (case, M, N, K, kind)
+        torch.cuda.synchronize()
+        full = out.to(torch.float32).cpu().numpy()
+        assert np.isnan(full[:, N:]).all()           # columns past N are not written
+        got = full[:, :N]
+        ref = A.astype(np.float64) @ W.astype(np.float64).T + bias
+        want = O.gelu_tanh(ref) if kind == 2 else ref
+        tol = 1e-4 if kind == 1 else 2.0 ** -8
+        err = np.abs(got - want) / (np.abs(want) + 1.0)
+        assert np.isfinite(got).all() and err.max() <= tol, (case, M, N, K, kind, err.max())
+
+
 def test_gemm_gated_residual_epilogue(torch, B):
     M, N, K, n_req = 333, 512, 128, 3
     A, W = rnd(1, "A", (M, K)), rnd(2, "W", (N, K), 0.05)
@@ -267,6 +297,43 @@ def test_attention_against_oracle(torch, B, dh, H, lens, mode):
         sl = slice(cu[s], cu[s + 1])
         ref = O.multi_head_attention(q[sl].astype(np.float64), k[sl].astype(np.float64), v[sl].astype(np.float64), H)
         assert max_abs(got[sl], ref) < 2e-2 and rel_l2(got[sl], ref) < 1e-2, (s, L)
+
+
+@pytest.mark.parametrize("dh,H", [(64, 2), (128, 1)])
+def test_attention_seeded_random_segment_lists(torch, B, dh, H):
+    """Six seeded lists of 1..6 segments of 1..700 tokens (plain form): packed offsets, ragged
+    query and key tiles, segments shorter than a tile next to long ones."""
+    rng = np.random.default_rng(777 + dh)
+    ip = lambda a: a.ctypes.data_as(C.POINTER(C.c_int))
+    for case in range(6):
+        lens = [int(v) for v in rng.integers(1, 701, int(rng.integers(1, 7)))]
+        d = H * dh
+        cu = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+        n = int(cu[-1])
+        q, k, v = (rnd(20 * case + s, nm, (n, d)) for s, nm in ((1, "q"), (2, "k"), (3, "v")))
+        q = synth.round_bf16(q * 1.5)
+        vt_off = np.zeros(len(lens), np.int32)
+        col = 0
+        for s, L in enumerate(lens):
+            vt_off[s] = col
+            col += (L + 63) // 64 * 64
+        vt = np.zeros((H, dh, col), np.float32)
+        for s, L in enumerate(lens):
+            vt[:, :, vt_off[s]:vt_off[s] + L] = v[cu[s]:cu[s + 1]].reshape(L, H, dh).transpose(1, 2, 0)
+        dq, dk, dvt = to_dev_bf16(torch, q), to_dev_bf16(torch, k), to_dev_bf16(torch, vt)
+        o = torch.full((n, d), float("nan"), dtype=torch.bfloat16, device="cuda")
+        wb = B.dit_op_attention_work_bytes(len(lens), ip(cu))
+        work = torch.empty(wb, dtype=torch.uint8, device="cuda")
+        st = B.dit_op_attention(None, dq.data_ptr(), d, dk.data_ptr(), d, dvt.data_ptr(), col, o.data_ptr(), d, H, dh,
+                                len(lens), ip(cu), ip(cu), ip(vt_off), work.data_ptr(), wb, 0, 0.0)
+        assert st == 0, (case, lens)
+        torch.cuda.synchronize()
+        got = bf16_to_np(o)
+        assert np.isfinite(got).all(), (case, lens)
+        for s, L in enumerate(lens):
+            sl = slice(cu[s], cu[s + 1])
+            ref = O.multi_head_attention(q[sl].astype(np.float64), k[sl].astype(np.float64), v[sl].astype(np.float64), H)
+            assert max_abs(got[sl], ref) < 2e-2 and rel_l2(got[sl], ref) < 1e-2, (case, s, L)
 
 
 def test_attention_identical_keys_returns_mean_of_v(torch, B):
