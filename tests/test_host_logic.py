@@ -111,3 +111,31 @@ def test_calls_fail_cleanly_without_buffers(B):
     assert B.dit_op_gemm(None, 256, 64, 256, 64, None, 4, 4, 65, 0, 256, 4, None, 0, None) == 2
     assert B.dit_op_attention_work_bytes(0, None) == 0
     m.close()
+
+
+def test_profiler_tool_host_logic():
+    """The offline profiler's CPU-side pieces: the paper's 20 % batching rule (Appendix "Impact of
+    Batch Size"), request-spec parsing, token counts and the decoder's product flop count."""
+    from paper_2510_02838_amd import stage_profile as SP
+    # largest B whose latency stays below 1.2 x latency(B = 1); B = 1 when even B = 2 exceeds it
+    assert SP.optimal_batch({1: 1.0, 2: 1.05, 3: 1.19, 4: 1.21, 8: 2.0}) == 3
+    assert SP.optimal_batch({1: 1.0, 2: 1.3, 4: 1.1}) == 4          # the rule looks at every B, not the first failure
+    assert SP.optimal_batch({1: 2.0, 2: 2.5}) == 1
+    cfg = synth.CONFIGS["sd3"]
+    assert SP._latent_dims(cfg, "1024") == (1, 128, 128)
+    assert SP._latent_dims(cfg, "480x832") == (1, 60, 104)
+    assert SP._latent_dims(cfg, "81x480x832") == (21, 60, 104)
+    assert SP._tokens(cfg["arch"], (1, 128, 128, 154)) == 4096 + 154
+    # decoder flops by hand for a one-level decoder at a 4 x 4 latent: conv_in, two mid residual
+    # blocks, the attention's four 1x1 products and two pixel products, one level block, conv_out
+    arch = dict(latent_ch=4, out_ch=3, channels=(128,), n_res=1)
+    px, c = 16, 128
+    conv = lambda cin, cout, k: 2.0 * px * k * k * cin * cout
+    want = conv(4, c, 3) + 3 * 2 * conv(c, c, 3) + 4 * conv(c, c, 1) + 4.0 * px * px * c + conv(c, 3, 3)
+    assert SP.decoder_flops(arch, 4, 4) == want
+    # a level change adds the shortcut and quadruples the pixels after the upsampling convolution
+    arch2 = dict(latent_ch=4, out_ch=3, channels=(128, 64), n_res=1)
+    up = 2.0 * (4 * px) * 9 * c * c
+    lvl1 = 2.0 * (4 * px) * 9 * (c * 64 + 64 * 64) + 2.0 * (4 * px) * c * 64
+    want2 = want - conv(c, 3, 3) + up + lvl1 + 2.0 * (4 * px) * 9 * 64 * 3
+    assert SP.decoder_flops(arch2, 4, 4) == want2
