@@ -11,7 +11,7 @@
  *   channel count changes; GN = GroupNorm(32 groups, eps 1e-6, affine); all convolutions have a
  *   bias and zero padding.
  *
- * Conventions are those of dit.h.  One latent per call.
+ * Conventions are those of dit.h.
  */
 #ifndef DIT_DECODER_H
 #define DIT_DECODER_H
@@ -38,10 +38,11 @@ dit_status dec_create(const dec_config* cfg, int device, void* hip_stream, dec_c
 void       dec_destroy(dec_ctx* ctx);
 const char* dec_last_error(const dec_ctx* ctx);
 
-/* Bytes of the weight arena and of the workspace for a latent of h x w (0 for an invalid size:
- * h, w >= 1 and (h*w) % 64 == 0 so that the mid-block attention product has whole k-slabs). */
+/* Bytes of the weight arena and of the workspace for n latents of h x w (0 for an invalid size:
+ * h, w >= 1 and (h*w) % 64 == 0 so that the mid-block attention product has whole k-slabs;
+ * 1 <= n <= 64 and, for n > 1, (h*w) % 256 == 0 so that no group-norm chunk straddles images). */
 size_t dec_weight_bytes(const dec_ctx* ctx);
-size_t dec_workspace_bytes(const dec_ctx* ctx, int h, int w);
+size_t dec_workspace_bytes(const dec_ctx* ctx, int n, int h, int w);
 dit_status dec_bind(dec_ctx* ctx, void* dev_weights, size_t weight_bytes, void* dev_workspace,
                     size_t workspace_bytes);
 
@@ -55,12 +56,15 @@ dit_status dec_tensor_info(const dec_ctx* ctx, int index, char* name, size_t nam
 dit_status dec_set_tensor(dec_ctx* ctx, const char* name, const float* host_src, size_t n);
 dit_status dec_get_tensor(dec_ctx* ctx, const char* name, float* host_dst, size_t n);
 
-/* Decodes one latent.  dev_latent: dev float32 [latent_ch][h][w] (the layout of the Diffuse
- * stage's latents with one frame); dev_image: dev float32, channels-last
- * [h*2^(n_levels-1)][w*2^(n_levels-1)][out_ch].  Asynchronous on the context's stream. */
-dit_status dec_forward(dec_ctx* ctx, int h, int w, const float* dev_latent, float* dev_image);
+/* Decodes a batch of n same-size latents (the paper batches the Decode stage like the others:
+ * Appendix "Impact of Batch Size").  dev_latents: dev float32 [n][latent_ch][h][w] (per latent
+ * the layout of the Diffuse stage's latents with one frame); dev_images: dev float32,
+ * channels-last [n][h*2^(n_levels-1)][w*2^(n_levels-1)][out_ch].  Every image's result is
+ * independent of its batch mates (statistics and attention are per image).  Asynchronous on
+ * the context's stream. */
+dit_status dec_forward(dec_ctx* ctx, int n, int h, int w, const float* dev_latents, float* dev_images);
 
-/* Capture points for tests (fp32 channels-last [pixels][C]): "mid.res0", "mid.attn", "up<l>". */
+/* Capture points for tests (fp32 channels-last [n * pixels][C]): "mid.res0", "mid.attn", "up<l>". */
 dit_status dec_set_tap(dec_ctx* ctx, const char* point, void* dev_dst, size_t bytes);
 void       dec_clear_taps(dec_ctx* ctx);
 

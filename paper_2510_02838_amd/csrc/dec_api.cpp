@@ -114,18 +114,29 @@ struct Layout {
 constexpr size_t PARTIAL_BYTES = (size_t)256 * 128 * 128 * 4;
 
 // latent sides 1..4096, h*w a multiple of 64 (whole k-slabs in the attention products) and at
-// most 65536 (the score matrix is held whole); the final image at most 65535 rows and, with its
-// border and the widest level, below 2^32 elements (32-bit offsets in the kernels)
-bool size_ok(const dec_ctx* c, int h, int w) {
+// most 65536 (the score matrix is held whole); the final image at most 65535 rows and, as a
+// stack of n bordered images of the widest level, below 2^32 elements (32-bit offsets in the
+// kernels); n images: 1..GN_MAX_BATCH, and with n > 1 h*w a multiple of 256 (group-norm chunks
+// must not straddle images)
+bool size_ok(const dec_ctx* c, int n, int h, int w) {
   if (!(h >= 1 && w >= 1 && h <= 4096 && w <= 4096 && ((long long)h * w) % 64 == 0 && (long long)h * w <= 65536)) return false;
+  if (n < 1 || n > GN_MAX_BATCH || (n > 1 && ((long long)h * w) % 256 != 0)) return false;
   const int up = 1 << (c->cfg.n_levels - 1);
-  int maxc = 64;
-  for (int l = 0; l < c->cfg.n_levels; ++l) maxc = std::max(maxc, c->cfg.channels[l]);
   const long long Hf = (long long)h * up, Wf = (long long)w * up;
-  return Hf <= 65535 && (Hf + 2) * (Wf + 2) * maxc < (1LL << 32) && Hf * Wf < (1LL << 31) / 4;
+  if (Hf > 65535 || n * Hf * Wf >= (1LL << 31) / 4) return false;
+  // the widest bordered stack of each level: its own width, and the previous level's after the upsampling
+  long long H = h, W = w, worst = 0;
+  int prev = std::max(c->cfg.channels[0], 64);
+  for (int l = 0; l < c->cfg.n_levels; ++l) {
+    const int ch = c->cfg.channels[l];
+    worst = std::max(worst, n * (H + 2) * (W + 2) * std::max(ch, prev));
+    prev = ch;
+    if (l != c->cfg.n_levels - 1) { H *= 2; W *= 2; worst = std::max(worst, n * (H + 2) * (W + 2) * ch); }
+  }
+  return worst < (1LL << 32);
 }
 
-void plan(const dec_ctx* c, int h, int w, Layout& L) {
+void plan(const dec_ctx* c, int n, int h, int w, Layout& L) {
   const dec_config& g = c->cfg;
   const int up = 1 << (g.n_levels - 1);
   L.Hf = h * up; L.Wf = w * up;
@@ -147,6 +158,7 @@ void plan(const dec_ctx* c, int h, int w, Layout& L) {
       max_x = std::max(max_x, (size_t)H * W * ch);
     }
   }
+  max_x *= n; max_img *= n;                                  // n streams / bordered images back to back
   const size_t C0 = g.channels[0];
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o += rup(bytes, 256); return at; };
@@ -154,14 +166,14 @@ void plan(const dec_ctx* c, int h, int w, Layout& L) {
   L.xa = take(max_x * 4); L.xb = take(max_x * 4); L.t = take(max_x * 4);
   L.img = take(max_img * 2 + 4096);
   L.act = take(max_x * 2);                                    // bf16 copy of the stream (1x1 shortcuts, attention input)
-  L.q = take((size_t)L.P0 * C0 * 2); L.k = take((size_t)L.P0pad * C0 * 2); L.v = take((size_t)L.P0 * C0 * 2);
+  L.q = take((size_t)n * L.P0 * C0 * 2); L.k = take(((size_t)(n - 1) * L.P0 + L.P0pad) * C0 * 2); L.v = take((size_t)n * L.P0 * C0 * 2);
   L.vt = take(rup(C0, 256) * rup(L.P0, 64) * 2);            // read as a second operand: rows up to a multiple of 256
   L.sc = take((size_t)L.P0 * L.P0 * 4);
   L.pm = take((size_t)L.P0 * rup(L.P0, 64) * 2);
   // channel sums per chunk of 64 pixels at least (the smallest wave height of a product tile)
-  L.gnp = take(std::max(group_norm_partial_bytes((long long)L.Hf * L.Wf, 1024), max_x / 64 * 8 + 2 * 1024 * 8));
+  L.gnp = take(std::max(group_norm_partial_bytes((long long)n * L.Hf * L.Wf, 1024), max_x / 64 * 8 + 2 * 1024 * 8));
   L.gst = take(GN_STATS_BYTES);
-  L.out4 = take((size_t)L.Hf * L.Wf * 4 * 4);
+  L.out4 = take((size_t)n * L.Hf * L.Wf * 4 * 4);
   L.partial = take(PARTIAL_BYTES);
   L.total = o;
 }
@@ -179,6 +191,7 @@ GemmProblem prob(const bf16_t* A, int lda, const bf16_t* W, int ldw, const float
 
 struct Fwd {
   dec_ctx* c; const Layout& L; unsigned char* ws; hipStream_t s;
+  int B;                                   // images in this call
   // the buffer whose per-chunk channel sums the last convolution left in the group-norm scratch
   mutable const float* stats_of = nullptr;
   mutable int stats_chunks = 0;
@@ -196,23 +209,25 @@ struct Fwd {
   // 3x3 convolution of the bordered bf16 image `img` (H x W, cin_pad channels) into fp32 rows
   void conv3(const std::string& name, const bf16_t* img, int H, int W, int kind, float* out, int ldc, bool sums = true) const {
     const DTensor* t = find(c, name + ".w");
-    GemmProblem p = prob(img, t->cin_pad, Wm(c, name + ".w"), t->ld, Wv(c, name + ".b"), H * W, t->cols_out,
+    GemmProblem p = prob(img, t->cin_pad, Wm(c, name + ".w"), t->ld, Wv(c, name + ".b"), B * H * W, t->cols_out,
                          9 * t->cin_pad, kind, out, ldc);
-    p.conv_w = W; p.conv_cin = t->cin_pad;
+    p.conv_w = W; p.conv_cin = t->cin_pad; p.conv_img = H * W;
     const bool want = sums && (kind == OUT_F32 || kind == OUT_RESID_F32);   // a group norm reads `out` next
     if (want) p.stats = at<float>(L.gnp);
     const int tile = gemm({p});
     if (want) {
       const int rows = gemm_stats_rows(tile);
-      stats_of = out; stats_chunks = (H * W + 2 * rows - 1) / (2 * rows) * 2;
+      // chunks per image: one per wave row of a tile (a lone image may end inside a tile; with
+      // several, H*W is a multiple of every chunk height)
+      stats_of = out; stats_chunks = B == 1 ? (H * W + 2 * rows - 1) / (2 * rows) * 2 : H * W / rows;
     }
   }
   void gn(const std::string& name, const float* x, bf16_t* out, int H, int W, int C, int silu, int pad) const {
     launch_group_norm(s, x, Wv(c, name + ".g"), Wv(c, name + ".b"), out, at<float>(L.gnp), at<float2>(L.gst), H, W, C,
-                      GROUPS, silu, pad, x == stats_of ? stats_chunks : 0);
+                      GROUPS, silu, pad, x == stats_of ? stats_chunks : 0, B);
   }
   void zero_img(int H, int W, int C) const {       // the border must be zero; the interior is overwritten
-    launch_zero_border(s, at<bf16_t>(L.img), H, W, C);
+    launch_zero_border(s, at<bf16_t>(L.img), H, W, C, B);
   }
   // x (cin channels, in `x`) -> result (cout channels) in `y`; y == x when cin == cout
   void res(const std::string& name, float* x, float* y, int H, int W, int cin, int cout) const {
@@ -222,9 +237,9 @@ struct Fwd {
     gn(name + ".gn1", x, img, H, W, cin, 1, 1);
     conv3(name + ".conv1", img, H, W, OUT_F32, t, cout);
     if (cin != cout) {
-      launch_cast_bf16(s, x, at<bf16_t>(L.act), (long long)H * W * cin);
+      launch_cast_bf16(s, x, at<bf16_t>(L.act), (long long)B * H * W * cin);
       gemm({prob(at<bf16_t>(L.act), cin, Wm(c, name + ".short.w"), Wld(c, name + ".short.w"), Wv(c, name + ".short.b"),
-                 H * W, cout, cin, OUT_F32, y, cout)});
+                 B * H * W, cout, cin, OUT_F32, y, cout)});
     }
     zero_img(H, W, cout);
     gn(name + ".gn2", t, img, H, W, cout, 1, 1);
@@ -291,10 +306,10 @@ void dec_destroy(dec_ctx* c) {
 }
 const char* dec_last_error(const dec_ctx* c) { return c ? c->err.c_str() : "null context"; }
 size_t dec_weight_bytes(const dec_ctx* c) { return c ? c->weight_bytes : 0; }
-size_t dec_workspace_bytes(const dec_ctx* c, int h, int w) {
-  if (!c || !size_ok(c, h, w)) return 0;
+size_t dec_workspace_bytes(const dec_ctx* c, int n, int h, int w) {
+  if (!c || !size_ok(c, n, h, w)) return 0;
   Layout L;
-  plan(c, h, w, L);
+  plan(c, n, h, w, L);
   return L.total;
 }
 
@@ -392,19 +407,20 @@ dit_status dec_set_tap(dec_ctx* c, const char* point, void* dst, size_t bytes) {
 }
 void dec_clear_taps(dec_ctx* c) { if (c) c->taps.clear(); }
 
-dit_status dec_forward(dec_ctx* c, int h, int w, const float* latent, float* image) {
+dit_status dec_forward(dec_ctx* c, int n, int h, int w, const float* latent, float* image) {
   if (!c) return DIT_EINVAL;
   if (!c->weights || !c->ws) return dfail(c, DIT_EINVAL, "dec_bind has not been called");
   if (!latent || !image) return dfail(c, DIT_EINVAL, "null latent or image");
-  if (!size_ok(c, h, w))
-    return dfail(c, DIT_ESHAPE, "latent %d x %d: sides 1..4096, pixel count a multiple of 64 and at most 65536, image below 2^32 elements per level", h, w);
+  if (!size_ok(c, n, h, w))
+    return dfail(c, DIT_ESHAPE, "%d latent(s) of %d x %d: sides 1..4096, pixel count a multiple of 64 (256 for a batch) and at most 65536, "
+                 "1..%d images, their bordered stack below 2^32 elements per level", n, h, w, GN_MAX_BATCH);
   const dec_config& g = c->cfg;
   DHIP(c, hipSetDevice(c->device));
   Layout L;
-  plan(c, h, w, L);
+  plan(c, n, h, w, L);
   if (L.total > c->ws_bytes) return dfail(c, DIT_ENOMEM, "workspace has %zu bytes, this call needs %zu", c->ws_bytes, L.total);
   hipStream_t s = c->stream;
-  Fwd F{c, L, c->ws, s};
+  Fwd F{c, L, c->ws, s, n};
   // identity column map of the mid-block's value transpose
   if (c->map_done) DHIP(c, hipEventSynchronize(c->map_done));
   else DHIP(c, hipEventCreateWithFlags(&c->map_done, hipEventDisableTiming));
@@ -418,32 +434,38 @@ dit_status dec_forward(dec_ctx* c, int h, int w, const float* latent, float* ima
   float* xa = F.at<float>(L.xa); float* xb = F.at<float>(L.xb);
   bf16_t* img = F.at<bf16_t>(L.img);
   int H = h, W = w;
-  // conv_in: latent (channels-first fp32) -> bordered bf16 image with the channels padded to 64
+  // conv_in: latents (channels-first fp32) -> bordered bf16 images with the channels padded to 64
   const DTensor* tin = find(c, "conv_in.w");
-  launch_fill_u16(s, img, (long long)(H + 2) * (W + 2) * tin->cin_pad, 0);
-  launch_latent_to_image(s, latent, img, g.latent_ch, H, W, tin->cin_pad);
+  launch_fill_u16(s, img, (long long)n * (H + 2) * (W + 2) * tin->cin_pad, 0);
+  launch_latent_to_image(s, latent, img, g.latent_ch, H, W, tin->cin_pad, n);
   F.conv3("conv_in", img, H, W, OUT_F32, xa, C0);
   // mid block
   F.res("mid.res0", xa, xa, H, W, C0, C0);
-  DTAP("mid.res0", xa, (size_t)P0 * C0 * 4);
+  DTAP("mid.res0", xa, (size_t)n * P0 * C0 * 4);
   {
     bf16_t* hn = F.at<bf16_t>(L.act);
     bf16_t* q = F.at<bf16_t>(L.q); bf16_t* k = F.at<bf16_t>(L.k); bf16_t* v = F.at<bf16_t>(L.v);
     bf16_t* vt = F.at<bf16_t>(L.vt); float* sc = F.at<float>(L.sc); bf16_t* pm = F.at<bf16_t>(L.pm);
+    const int M0 = n * P0;
     F.gn("mid.attn.gn", xa, hn, H, W, C0, 0, 0);
-    F.gemm({prob(hn, C0, Wm(c, "mid.attn.q.w"), Wld(c, "mid.attn.q.w"), Wv(c, "mid.attn.q.b"), P0, C0, C0, OUT_BF16, q, C0),
-            prob(hn, C0, Wm(c, "mid.attn.k.w"), Wld(c, "mid.attn.k.w"), Wv(c, "mid.attn.k.b"), P0, C0, C0, OUT_BF16, k, C0),
-            prob(hn, C0, Wm(c, "mid.attn.v.w"), Wld(c, "mid.attn.v.w"), Wv(c, "mid.attn.v.b"), P0, C0, C0, OUT_BF16, v, C0)});
-    // scores = q k^T: k is the second operand as it stands ([keys][C], C contiguous)
-    F.gemm({prob(q, C0, k, C0, nullptr, P0, P0, C0, OUT_F32, sc, P0)});
-    launch_softmax_rows(s, sc, P0, pm, P0c, P0, P0, 1.4426950408889634f / sqrtf((float)C0));
-    // o = P v: second operand v^T [C][keys], made by the value transpose in 128-channel slices
-    launch_v_transpose(s, v, C0, 0, C0 / 128, 128, F.at<int>(L.map), P0c, vt, P0c);
-    F.gemm({prob(pm, P0c, vt, P0c, nullptr, P0, C0, P0c, OUT_BF16, q, C0)});       // (q's buffer is free again)
-    F.gemm({prob(q, C0, Wm(c, "mid.attn.proj.w"), Wld(c, "mid.attn.proj.w"), Wv(c, "mid.attn.proj.b"), P0, C0, C0,
+    F.gemm({prob(hn, C0, Wm(c, "mid.attn.q.w"), Wld(c, "mid.attn.q.w"), Wv(c, "mid.attn.q.b"), M0, C0, C0, OUT_BF16, q, C0),
+            prob(hn, C0, Wm(c, "mid.attn.k.w"), Wld(c, "mid.attn.k.w"), Wv(c, "mid.attn.k.b"), M0, C0, C0, OUT_BF16, k, C0),
+            prob(hn, C0, Wm(c, "mid.attn.v.w"), Wld(c, "mid.attn.v.w"), Wv(c, "mid.attn.v.b"), M0, C0, C0, OUT_BF16, v, C0)});
+    // per image: scores = q k^T (k is the second operand as it stands: [keys][C], C contiguous;
+    // the tile may read rows of the next image or of the padding: their columns are not stored),
+    // softmax, o = P v with v^T [C][keys] from the value transpose in 128-channel slices; o goes
+    // to hn, which is free after the three products
+    for (int b = 0; b < n; ++b) {
+      const size_t ro = (size_t)b * P0 * C0;
+      F.gemm({prob(q + ro, C0, k + ro, C0, nullptr, P0, P0, C0, OUT_F32, sc, P0)});
+      launch_softmax_rows(s, sc, P0, pm, P0c, P0, P0, 1.4426950408889634f / sqrtf((float)C0));
+      launch_v_transpose(s, v + ro, C0, 0, C0 / 128, 128, F.at<int>(L.map), P0c, vt, P0c);
+      F.gemm({prob(pm, P0c, vt, P0c, nullptr, P0, C0, P0c, OUT_BF16, hn + ro, C0)});
+    }
+    F.gemm({prob(hn, C0, Wm(c, "mid.attn.proj.w"), Wld(c, "mid.attn.proj.w"), Wv(c, "mid.attn.proj.b"), M0, C0, C0,
                  OUT_RESID_F32, xa, C0)});
   }
-  DTAP("mid.attn", xa, (size_t)P0 * C0 * 4);
+  DTAP("mid.attn", xa, (size_t)n * P0 * C0 * 4);
   F.res("mid.res1", xa, xa, H, W, C0, C0);
   // up levels
   float* x = xa; float* other = xb;
@@ -457,23 +479,23 @@ dit_status dec_forward(dec_ctx* c, int h, int w, const float* latent, float* ima
       else F.res(name, x, x, H, W, ch, ch);
     }
     prev = ch;
-    DTAP("up" + std::to_string(l), x, (size_t)H * W * ch * 4);
+    DTAP("up" + std::to_string(l), x, (size_t)n * H * W * ch * 4);
     if (l != g.n_levels - 1) {
-      launch_zero_border(s, img, 2 * H, 2 * W, ch);
-      launch_upsample_pad(s, x, img, H, W, ch);
+      launch_zero_border(s, img, 2 * H, 2 * W, ch, n);
+      launch_upsample_pad(s, x, img, H, W, ch, n);
       H *= 2; W *= 2;
       F.conv3("up" + std::to_string(l) + ".upconv", img, H, W, OUT_F32, other, ch);
       std::swap(x, other);
     }
   }
-  // output: GN + SiLU + conv to out_ch channels (product rows are 4 wide, then compacted)
+  // output: GN + SiLU + conv to out_ch channels
   F.zero_img(H, W, prev);
   F.gn("out.gn", x, img, H, W, prev, 1, 1);
   {
     const DTensor* to = find(c, "conv_out.w");
-    if (!launch_conv3_small(s, img, Wm(c, "conv_out.w"), to->ld, Wv(c, "conv_out.b"), image, H, W, to->cin_pad, g.out_ch)) {
-      F.conv3("conv_out", img, H, W, OUT_F32, F.at<float>(L.out4), 4, false);     // wide last level: as a product
-      launch_compact_rows(s, F.at<float>(L.out4), 4, image, (long long)H * W, g.out_ch);
+    if (!launch_conv3_small(s, img, Wm(c, "conv_out.w"), to->ld, Wv(c, "conv_out.b"), image, H, W, to->cin_pad, g.out_ch, n)) {
+      F.conv3("conv_out", img, H, W, OUT_F32, F.at<float>(L.out4), 4, false);     // wide last level: as a product, rows 4 wide, then compacted
+      launch_compact_rows(s, F.at<float>(L.out4), 4, image, (long long)n * H * W, g.out_ch);
     }
   }
   DHIP(c, hipGetLastError());

@@ -1,7 +1,8 @@
 // Row-wise kernels of the Decode stage (AutoencoderKL-style convolutional decoder).  Activations
 // are channels-last; the residual stream is fp32 [pixels][C]; inputs of 3x3 convolutions are
 // bf16 images with a one-pixel zero border, [(H+2)*(W+2)][C], so that the convolution is a
-// matrix product with shifted row addresses (gemm.hip) and needs no masking.
+// matrix product with shifted row addresses (gemm.hip) and needs no masking.  A batch of B
+// same-size images is B such streams / bordered images back to back.
 #include "dit_internal.h"
 
 namespace dit {
@@ -20,25 +21,29 @@ __device__ __forceinline__ long long dst_pixel(int y, int x, int W, int pad) {
 }
 }  // namespace
 
-// latent fp32 channels-first [C][H][W] -> bf16 bordered channels-last [(H+2)(W+2)][Cpad], channels
-// from C on are zero (the border is zero from a fill of the whole buffer by the caller)
+// latents fp32 channels-first [B][C][H][W] -> bf16 bordered channels-last [B][(H+2)(W+2)][Cpad],
+// channels from C on are zero (the border is zero from a fill of the whole buffer by the caller)
 __global__ __launch_bounds__(256) void latent_to_image_kernel(const float* __restrict__ z, bf16_t* __restrict__ out,
-                                                              int C, int H, int W, int Cpad) {
+                                                              int C, int H, int W, int Cpad, int B) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= (long long)H * W * C) return;
-  const int c = (int)(i % C);
-  const long long p = i / C;
+  const long long per = (long long)H * W * C;
+  if (i >= per * B) return;
+  const int b = (int)(i / per);
+  const long long r = i - b * per;
+  const int c = (int)(r % C);
+  const long long p = r / C;
   const int y = (int)(p / W), x = (int)(p % W);
-  out[dst_pixel(y, x, W, 1) * Cpad + c] = d_f2bf(z[((long long)c * H + y) * W + x]);
+  out[((long long)b * (H + 2) * (W + 2) + dst_pixel(y, x, W, 1)) * Cpad + c] = d_f2bf(z[(((long long)b * C + c) * H + y) * W + x]);
 }
 
-void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad) {
-  const long long n = (long long)H * W * C;
-  if (n) hipLaunchKernelGGL(latent_to_image_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, z, out, C, H, W, Cpad);
+void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad, int B) {
+  const long long n = (long long)B * H * W * C;
+  if (n) hipLaunchKernelGGL(latent_to_image_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, z, out, C, H, W, Cpad, B);
 }
 
 // zero border of a bordered image [(H+2)(W+2)][C]: rows 0 and H+1, columns 0 and W+1
 __global__ __launch_bounds__(256) void zero_border_kernel(bf16_t* __restrict__ img, int H, int W, int C) {
+  img += (size_t)blockIdx.y * (H + 2) * (W + 2) * C;       // one bordered image per blockIdx.y
   const int o8 = C >> 3;                                   // 16-byte pieces per pixel
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   const long long nb = 2LL * (W + 2) + 2LL * H;            // border pixels
@@ -51,9 +56,9 @@ __global__ __launch_bounds__(256) void zero_border_kernel(bf16_t* __restrict__ i
   else { const long long r = b - 2LL * (W + 2); pix = (r / 2 + 1) * (W + 2) + ((r & 1) ? W + 1 : 0); }
   *(uint4*)(img + pix * C + c) = make_uint4(0, 0, 0, 0);
 }
-void launch_zero_border(hipStream_t s, bf16_t* img, int H, int W, int C) {
+void launch_zero_border(hipStream_t s, bf16_t* img, int H, int W, int C, int B) {
   const long long n = (2LL * (W + 2) + 2LL * H) * (C / 8);
-  if (n) hipLaunchKernelGGL(zero_border_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, img, H, W, C);
+  if (n && B) hipLaunchKernelGGL(zero_border_kernel, dim3((unsigned)((n + 255) / 256), B), dim3(256), 0, s, img, H, W, C);
 }
 
 // ---- group norm ---------------------------------------------------------------------------
@@ -111,6 +116,10 @@ __global__ __launch_bounds__(256) void gn_finalize_kernel(const float* __restric
   __shared__ double rs[256], rq[256];
   const int g = blockIdx.x, cpg = C / groups, tid = threadIdx.x;
   const int shares = gridDim.y, sh = blockIdx.y;
+  const int img = blockIdx.z;                    // chunks, P: per image; an image's chunks are consecutive
+  partial += (size_t)img * chunks * C * 2;
+  stats += img * groups;
+  part += img * groups * shares;
   const int c0 = (int)((long long)chunks * sh / shares), c1 = (int)((long long)chunks * (sh + 1) / shares);
   double a = 0.0, b = 0.0;
   for (int ch = c0 + tid; ch < c1; ch += 256)
@@ -136,6 +145,8 @@ __global__ __launch_bounds__(64) void gn_combine_kernel(const double2* __restric
                                                         int shares, int cpg, int groups, long long P) {
   const int g = threadIdx.x;
   if (g >= groups) return;
+  part += blockIdx.x * groups * shares;          // one image per workgroup
+  stats += blockIdx.x * groups;
   double a = 0.0, b = 0.0;
   for (int s = 0; s < shares; ++s) { a += part[g * shares + s].x; b += part[g * shares + s].y; }
   const double n = (double)P * cpg, mean = a / n;
@@ -148,10 +159,14 @@ __global__ __launch_bounds__(64) void gn_combine_kernel(const double2* __restric
 __global__ __launch_bounds__(256) void gn_apply_kernel(const float* __restrict__ x, const float2* __restrict__ stats,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        bf16_t* __restrict__ out, int W, int C, int osh, int gsh,
-                                                       int silu, int pad) {
+                                                       int silu, int pad, int groups) {
   const int i = blockIdx.x * 256 + threadIdx.x;      // unit of 8 channels inside the row
   const int opc = C >> 3;                            // = 1 << osh
   if (i >= W * opc) return;
+  const int H = gridDim.y, img = blockIdx.z;         // one image per blockIdx.z
+  x += (size_t)img * H * W * C;
+  out += (size_t)img * (pad ? (size_t)(H + 2) * (W + 2) : (size_t)H * W) * C;
+  stats += img * groups;
   const int y = blockIdx.y, xx = i >> osh, c = (i & (opc - 1)) * 8;
   const float* xr = x + ((size_t)y * W + xx) * C + c;
   const float4 v0 = *(const float4*)xr, v1 = *(const float4*)(xr + 4);
@@ -171,13 +186,15 @@ __global__ __launch_bounds__(256) void gn_apply_kernel(const float* __restrict__
   *(uint4*)(out + dst_pixel(y, xx, W, pad) * C + c) = w;
 }
 
-// ready_chunks > 0: `partial` already holds the per-chunk channel sums of x (written by the
-// epilogue of the convolution that produced x, any chunk height): pass 1 is skipped.
+// B images of H x W; statistics per image and group.  ready_chunks > 0: `partial` already holds
+// that many per-chunk channel sums PER IMAGE (written by the epilogue of the convolution that
+// produced x; chunks do not straddle images): pass 1 is skipped.  With B > 1 the standalone
+// pass 1 needs H*W to be a multiple of its chunk (256 pixels).
 void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const float* beta, bf16_t* out,
                        float* partial, float2* stats, int H, int W, int C, int groups, int silu, int pad,
-                       int ready_chunks) {
+                       int ready_chunks, int B) {
   const long long P = (long long)H * W;
-  if (P == 0) return;
+  if (P == 0 || B == 0) return;
   int chunks = ready_chunks;
   int csh = 0;
   while ((1 << csh) < C) ++csh;                  // C = 1 << csh
@@ -186,15 +203,15 @@ void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const 
   if (chunks <= 0) {
     chunks = (int)((P + GN_CHUNK - 1) / GN_CHUNK);
     const int pix_par = 256 >> (csh - 2);
-    hipLaunchKernelGGL(gn_partial_kernel, dim3(chunks), dim3(256), (size_t)pix_par * C * 2 * sizeof(float), s, x, partial, P, C, csh - 2);
+    hipLaunchKernelGGL(gn_partial_kernel, dim3(chunks * B), dim3(256), (size_t)pix_par * C * 2 * sizeof(float), s, x, partial, P * B, C, csh - 2);
   }
-  // stats: [groups] float2 followed (256 bytes on) by the [groups][shares] float64 pairs of the two-stage form
+  // stats: [B][groups] float2, then (GN_STATS_HEAD bytes on) the [B][groups][shares] float64 pairs of the two-stage form
   const int shares = chunks >= 4096 ? 16 : (chunks >= 1024 ? 4 : 1);
-  double2* part = (double2*)((unsigned char*)stats + 256);
-  hipLaunchKernelGGL(gn_finalize_kernel, dim3(groups, shares), dim3(256), 0, s, partial, stats, part, chunks, C, groups, P);
-  if (shares > 1) hipLaunchKernelGGL(gn_combine_kernel, dim3(1), dim3(64), 0, s, part, stats, shares, C / groups, groups, P);
+  double2* part = (double2*)((unsigned char*)stats + GN_STATS_HEAD);
+  hipLaunchKernelGGL(gn_finalize_kernel, dim3(groups, shares, B), dim3(256), 0, s, partial, stats, part, chunks, C, groups, P);
+  if (shares > 1) hipLaunchKernelGGL(gn_combine_kernel, dim3(B), dim3(64), 0, s, part, stats, shares, C / groups, groups, P);
   const int units = W * (C >> 3);
-  hipLaunchKernelGGL(gn_apply_kernel, dim3((units + 255) / 256, H), dim3(256), 0, s, x, stats, gamma, beta, out, W, C, csh - 3, gsh, silu, pad);
+  hipLaunchKernelGGL(gn_apply_kernel, dim3((units + 255) / 256, H, B), dim3(256), 0, s, x, stats, gamma, beta, out, W, C, csh - 3, gsh, silu, pad, groups);
 }
 size_t group_norm_partial_bytes(long long pixels, int C) {
   return (size_t)((pixels + GN_CHUNK - 1) / GN_CHUNK) * C * 2 * sizeof(float);
@@ -207,6 +224,8 @@ __global__ __launch_bounds__(256) void upsample_pad_kernel(const float* __restri
   const int qpc = C >> 2;
   const int H2 = 2 * H, W2 = 2 * W;
   if (i >= (long long)H2 * W2 * qpc) return;
+  x += (size_t)blockIdx.y * H * W * C;               // one image per blockIdx.y
+  out += (size_t)blockIdx.y * (H2 + 2) * (W2 + 2) * C;
   const long long p = i / qpc;
   const int c = (int)(i % qpc) * 4;
   const int y = (int)(p / W2), xx = (int)(p % W2);
@@ -215,9 +234,9 @@ __global__ __launch_bounds__(256) void upsample_pad_kernel(const float* __restri
   w.x = d_pack2(v.x, v.y); w.y = d_pack2(v.z, v.w);
   *(uint2*)(out + dst_pixel(y, xx, W2, 1) * C + c) = w;
 }
-void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C) {
+void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C, int B) {
   const long long n = (long long)4 * H * W * (C / 4);
-  if (n) hipLaunchKernelGGL(upsample_pad_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, out, H, W, C);
+  if (n && B) hipLaunchKernelGGL(upsample_pad_kernel, dim3((unsigned)((n + 255) / 256), B), dim3(256), 0, s, x, out, H, W, C);
 }
 
 // fp32 -> bf16, 4 elements per thread (plain rows)
@@ -318,7 +337,7 @@ void launch_softmax_rows(hipStream_t s, const float* sc, int lds_, bf16_t* out, 
 template <int OC>
 __global__ __launch_bounds__(256) void conv3_small_kernel(const bf16_t* __restrict__ img, const bf16_t* __restrict__ w, int ldw,
                                                           const float* __restrict__ bias, float* __restrict__ out,
-                                                          int H, int W, int C, int lsh) {
+                                                          int H, int W, int C, int lsh, int B) {
   typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
   const int lane = threadIdx.x & 63;
   const int lpp = 1 << lsh;                         // lanes per pixel = C / 8
@@ -328,13 +347,15 @@ __global__ __launch_bounds__(256) void conv3_small_kernel(const bf16_t* __restri
   for (int tap = 0; tap < 9; ++tap)
 #pragma unroll
     for (int o = 0; o < OC; ++o) wr[tap][o] = *(const uint4*)(w + (size_t)o * ldw + tap * C + sub * 8);
-  const long long P = (long long)H * W;
+  const long long PI = (long long)H * W, P = PI * B;      // B images back to back
   const long long wave = (long long)blockIdx.x * 4 + (threadIdx.x >> 6), nwaves = (long long)gridDim.x * 4;
   for (long long p0 = wave * ppw; p0 < P; p0 += nwaves * ppw) {
     const long long p = p0 + pl;
     const bool ok = p < P;
     const long long pc = ok ? p : P - 1;
-    const int y = (int)(pc / W), x = (int)(pc % W);
+    const int bimg = (int)(pc / PI);
+    const long long pr = pc - bimg * PI;
+    const int y = (int)(pr / W) + bimg * (H + 2), x = (int)(pr % W);   // row in the stack of bordered images
     float acc[OC];
 #pragma unroll
     for (int o = 0; o < OC; ++o) acc[o] = 0.f;
@@ -363,9 +384,9 @@ __global__ __launch_bounds__(256) void conv3_small_kernel(const bf16_t* __restri
   }
 }
 bool launch_conv3_small(hipStream_t s, const bf16_t* img, const bf16_t* w, int ldw, const float* bias, float* out,
-                        int H, int W, int C, int OC) {
+                        int H, int W, int C, int OC, int B) {
   if (OC < 1 || OC > 4 || (C != 64 && C != 128 && C != 256 && C != 512)) return false;
-  const long long P = (long long)H * W;
+  const long long P = (long long)H * W * B;
   if (P == 0) return true;
   int lsh = 0;
   while ((8 << lsh) < C) ++lsh;
@@ -373,10 +394,10 @@ bool launch_conv3_small(hipStream_t s, const bf16_t* img, const bf16_t* w, int l
   const long long want = (groups + 3) / 4;
   dim3 g((unsigned)(want < 4096 ? want : 4096)), b(256);
   switch (OC) {
-    case 1: hipLaunchKernelGGL(conv3_small_kernel<1>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh); break;
-    case 2: hipLaunchKernelGGL(conv3_small_kernel<2>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh); break;
-    case 3: hipLaunchKernelGGL(conv3_small_kernel<3>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh); break;
-    default: hipLaunchKernelGGL(conv3_small_kernel<4>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh); break;
+    case 1: hipLaunchKernelGGL(conv3_small_kernel<1>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B); break;
+    case 2: hipLaunchKernelGGL(conv3_small_kernel<2>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B); break;
+    case 3: hipLaunchKernelGGL(conv3_small_kernel<3>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B); break;
+    default: hipLaunchKernelGGL(conv3_small_kernel<4>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B); break;
   }
   return true;
 }

@@ -42,10 +42,12 @@ struct GemmProblem {
   int out_kind; void* out; int ldc;
   const float* gate; int gate_stride; const int* row_req;  // OUT_RESID_F32 only
   QkNorm qk;                                               // OUT_QKNORM only
-  // 3x3 convolution as a product (conv_w > 0): A is a channels-last bf16 image with a one-pixel
-  // zero border, [(H+2)*(conv_w+2)][conv_cin]; row m of the product is output pixel (m / conv_w,
-  // m % conv_w), column index k = tap*conv_cin + c with tap = 3*ky + kx; conv_cin % 64 == 0, K = 9*conv_cin.
-  int conv_w = 0, conv_cin = 0;
+  // 3x3 convolution as a product (conv_w > 0): A is a stack of channels-last bf16 images with a
+  // one-pixel zero border each, [B][(H+2)*(conv_w+2)][conv_cin]; conv_img = H*conv_w pixels per
+  // image; row m of the product is pixel (r / conv_w, r % conv_w) of image m / conv_img,
+  // r = m % conv_img; column index k = tap*conv_cin + c with tap = 3*ky + kx; conv_cin % 64 == 0,
+  // K = 9*conv_cin.
+  int conv_w = 0, conv_cin = 0, conv_img = 1;
   // convolutions with OUT_F32 / OUT_RESID_F32 only, optional: per column n, the sum and the sum
   // of squares of the stored values over the rows of each (tile row, wave row) pair:
   // stats[(tile_row * 2 + wave_row)][N][2], rows of a pair = tile height / 2 (gemm_stats_rows)
@@ -153,26 +155,28 @@ void launch_rel_bias_table(hipStream_t s, const float* table, float* bias, int H
 
 // ---- Decode stage (convolutional decoder), channels-last activations ----------------------
 // latent fp32 [C][H][W] -> bf16 bordered image [(H+2)(W+2)][Cpad] (interior only; caller zero-fills)
-void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad);
-void launch_zero_border(hipStream_t s, bf16_t* img, int H, int W, int C);   // C % 8 == 0
+void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad, int B = 1);
+void launch_zero_border(hipStream_t s, bf16_t* img, int H, int W, int C, int B = 1);   // C % 8 == 0
 // GroupNorm (eps 1e-6, affine) of the fp32 stream x [H*W][C], optional SiLU, bf16 output with
 // (pad=1) or without a one-pixel border.  C in {64,128,256,512,1024}; partial: scratch of
 // group_norm_partial_bytes; stats: scratch of GN_STATS_BYTES (groups <= 32).  ready_chunks > 0: partial already holds
 // [ready_chunks][C][2] channel sums of x (GemmProblem::stats) and the statistics pass is skipped.
 size_t group_norm_partial_bytes(long long pixels, int C);
-constexpr size_t GN_STATS_BYTES = 256 + 32 * 16 * 16;
+constexpr int GN_MAX_BATCH = 64;
+constexpr size_t GN_STATS_HEAD = (size_t)GN_MAX_BATCH * 32 * 8;                       // [B][groups] float2
+constexpr size_t GN_STATS_BYTES = GN_STATS_HEAD + (size_t)GN_MAX_BATCH * 32 * 16 * 16;   // + [B][groups][shares] double2
 void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const float* beta, bf16_t* out,
                        float* partial, float2* stats, int H, int W, int C, int groups, int silu, int pad,
-                       int ready_chunks = 0);
+                       int ready_chunks = 0, int B = 1);   // B same-size images back to back, statistics per image
 // nearest 2x upsampling of x [H*W][C] fp32 into a bf16 bordered image of size 2H x 2W
-void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C);
+void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C, int B = 1);
 void launch_cast_bf16(hipStream_t s, const float* x, bf16_t* out, long long n);     // n % 4 == 0
 // out[r][j] = softmax_j(sc[r][j] * scale) as bf16, j < n; columns n..ldo-1 are set to zero
 void launch_softmax_rows(hipStream_t s, const float* sc, int lds_, bf16_t* out, int ldo, int rows, int n, float scale_log2);
 // 3x3 convolution of a bordered bf16 image to OC <= 4 fp32 channels without the matrix cores;
 // false (nothing launched) if the shape is outside its limits (C in {64,128,256,512}, OC <= 4)
 bool launch_conv3_small(hipStream_t s, const bf16_t* img, const bf16_t* w, int ldw, const float* bias, float* out,
-                        int H, int W, int C, int OC);
+                        int H, int W, int C, int OC, int B = 1);
 void launch_compact_rows(hipStream_t s, const float* src, int lds_, float* dst, long long P, int C);
 
 // weights

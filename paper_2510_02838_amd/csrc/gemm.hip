@@ -158,9 +158,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   for (int i = 0; i < LA; ++i) {
     int q = i * NT + tid, r = q / CPR, pc = q % CPR, c = pc ^ swz_key<BKT>(r);
     int m = m0 + r; if (m >= P.M) m = P.M - 1;            // clamp: rows past M are never stored
-    if constexpr (CONV) {    // top-left pixel of the 3x3 window in the bordered image
-      const int y = m / P.conv_w, x = m - y * P.conv_w;
-      ga[i] = (uint32_t)(y * (P.conv_w + 2) + x) * (uint32_t)P.conv_cin + c * 8;
+    if constexpr (CONV) {    // top-left pixel of the 3x3 window in the stack of bordered images
+      const int b = m / P.conv_img, r = m - b * P.conv_img;
+      const int y = r / P.conv_w, x = r - y * P.conv_w;
+      ga[i] = (uint32_t)((b * (P.conv_img / P.conv_w + 2) + y) * (P.conv_w + 2) + x) * (uint32_t)P.conv_cin + c * 8;
     } else {
       ga[i] = (uint32_t)m * (uint32_t)P.lda + c * 8;
     }
@@ -639,6 +640,8 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
   for (int i = 0; i < b.n; ++i) { conv = conv || b.p[i].conv_w > 0; plain = plain || b.p[i].conv_w <= 0; }
   if (conv) {     // convolutions: never mixed with plain products, three tile shapes
     if (plain) return -1;
+    for (int i = 0; i < b.n; ++i)        // whole images of whole rows
+      if (b.p[i].conv_img <= 0 || b.p[i].conv_img % b.p[i].conv_w || b.p[i].M % b.p[i].conv_img) return -1;
     if (tile == 1256256) launch_t<256, 256, 2, 4, 64, 2, 0, true>(s, b);
     else if (tile == 30128128) launch_t<128, 128, 2, 2, 64, 4, 0, true>(s, b);
     else { tile = 128128; launch_t<128, 128, 2, 2, 64, 2, 0, true>(s, b); }

@@ -20,14 +20,14 @@ _SIGS = {
     "dec_destroy": (None, [_vp]),
     "dec_last_error": (C.c_char_p, [_vp]),
     "dec_weight_bytes": (_sz, [_vp]),
-    "dec_workspace_bytes": (_sz, [_vp, _i, _i]),
+    "dec_workspace_bytes": (_sz, [_vp, _i, _i, _i]),
     "dec_bind": (_i, [_vp, _vp, _sz, _vp, _sz]),
     "dec_init_weights": (_i, [_vp, C.c_uint64, C.c_float]),
     "dec_tensor_count": (_i, [_vp]),
     "dec_tensor_info": (_i, [_vp, _i, C.c_char_p, _sz, _ip, _ip, _ip]),
     "dec_set_tensor": (_i, [_vp, C.c_char_p, _fp, _sz]),
     "dec_get_tensor": (_i, [_vp, C.c_char_p, _fp, _sz]),
-    "dec_forward": (_i, [_vp, _i, _i, _vp, _vp]),
+    "dec_forward": (_i, [_vp, _i, _i, _i, _vp, _vp]),
     "dec_set_tap": (_i, [_vp, C.c_char_p, _vp, _sz]),
     "dec_clear_taps": (None, [_vp]),
 }
@@ -82,14 +82,14 @@ class Decoder:
     def weight_bytes(self):
         return dec_weight_bytes(self.ctx)
 
-    def workspace_bytes(self, h, w):
-        return dec_workspace_bytes(self.ctx, h, w)
+    def workspace_bytes(self, h, w, n=1):
+        return dec_workspace_bytes(self.ctx, n, h, w)
 
     def up_factor(self):
         return 1 << (self.cfg.n_levels - 1)
 
-    def ensure_workspace(self, h, w):
-        need = self.workspace_bytes(h, w)
+    def ensure_workspace(self, h, w, n=1):
+        need = self.workspace_bytes(h, w, n)
         if need == 0:
             raise DitError(2, "invalid latent size")
         if self.workspace is None or self.workspace.numel() < need:
@@ -122,9 +122,9 @@ class Decoder:
         for name, arr in params.items():
             self.set_tensor(name, arr)
 
-    def forward(self, h, w, latent, image):
-        """latent: fp32 [latent_ch][h][w]; image: fp32 [h*f][w*f][out_ch], f = up_factor()."""
-        self.check(dec_forward(self.ctx, h, w, latent.data_ptr(), image.data_ptr()))
+    def forward(self, h, w, latent, image, n=1):
+        """latent: fp32 [n][latent_ch][h][w]; image: fp32 [n][h*f][w*f][out_ch], f = up_factor()."""
+        self.check(dec_forward(self.ctx, n, h, w, latent.data_ptr(), image.data_ptr()))
 
     def set_tap(self, point, tensor):
         self._keep[point] = tensor

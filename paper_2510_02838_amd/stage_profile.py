@@ -19,12 +19,13 @@ each for the stages before and after it:
 
     python -m paper_2510_02838_amd.stage_profile batch [--workload sd3] [--res 128,256,512] [--max-batch 32]
     python -m paper_2510_02838_amd.stage_profile grid  [--workload sd3|flux|wan] [--res ...]
-  decode  the Decode stage (AutoencoderKL-style decoder): latency, product flop rate and the
-          bytes held per image resolution (the paper: Encode and Decode are memory-bound and can
-          reach a higher peak memory than Diffuse).
+  decode  the Decode stage (AutoencoderKL-style decoder): latency against the number of same-size
+          latents per call, per image resolution, with the same 20 % rule; product flop rate and
+          the bytes held (the paper: Encode and Decode are memory-bound and can reach a higher
+          peak memory than Diffuse).
 
     python -m paper_2510_02838_amd.stage_profile encode [--encoder t5_xxl] [--lens 32,128,500] [--max-batch 64]
-    python -m paper_2510_02838_amd.stage_profile decode [--decoder ae_kl] [--res 256,512,1024]
+    python -m paper_2510_02838_amd.stage_profile decode [--decoder ae_kl] [--res 128,256,512,1024] [--max-batch 8]
     python -m paper_2510_02838_amd.stage_profile pipeline [--workload sd3|flux] [--res 512,1024] [--steps 28]
 
   pipeline  one request through all three stages on this GPU, the output of each feeding the next
@@ -240,30 +241,49 @@ def run_decode(args):
     m = X.Decoder(arch)
     f = m.up_factor()
     sizes = [int(v) // f for v in args.res.split(",")]
-    m.ensure_workspace(max(sizes), max(sizes))
-    m.init_weights(1, 0.02)
-    print("| image | latent | ms | product TFLOP/s | GFLOP | workspace GiB | weights MiB |", file=sys.stderr)
-    print("|---|---|---|---|---|---|---|", file=sys.stderr)
+    batches = [b for b in (1, 2, 4, 8, 16, 32) if b <= args.max_batch]
+    rows = []
+    first = True
     for n in sizes:
-        z = torch.from_numpy(synth.gaussian(3, "latent", arch["latent_ch"] * n * n).astype(np.float32)).cuda()
-        img = torch.empty((n * f, n * f, arch["out_ch"]), dtype=torch.float32, device="cuda")
-        m.forward(n, n, z, img)
-        torch.cuda.synchronize()
-        best = float("inf")
-        for _ in range(3):
-            t0 = time.perf_counter()
-            m.forward(n, n, z, img)
+        lat = {}
+        for b in batches:
+            ws = m.workspace_bytes(n, n, b)
+            if ws == 0:                                   # the batch form needs h*w % 256 == 0 and 32-bit offsets
+                continue
+            m.ensure_workspace(n, n, b)
+            if first:
+                m.init_weights(1, 0.02)
+                first = False
+            z = torch.from_numpy(synth.gaussian(3, "latent", b * arch["latent_ch"] * n * n).astype(np.float32)).cuda()
+            img = torch.empty((b, n * f, n * f, arch["out_ch"]), dtype=torch.float32, device="cuda")
+            m.forward(n, n, z, img, n=b)
             torch.cuda.synchronize()
-            best = min(best, time.perf_counter() - t0)
-        if not bool(torch.isfinite(img).all().item()):
-            raise RuntimeError("non-finite image")
-        fl = decoder_flops(arch, n, n)
-        ws = m.workspace_bytes(n, n)
-        row = {"table": "decode", "decoder": args.decoder, "image": n * f, "latent": n, "ms": best * 1e3,
-               "product_flops": fl, "tflops": fl / best / 1e12, "workspace_bytes": ws, "weight_bytes": m.weight_bytes()}
-        print(json.dumps(row), flush=True)
-        print(f"| {n * f}x{n * f} | {n}x{n} | {best * 1e3:.2f} | {fl / best / 1e12:.0f} | {fl / 1e9:.0f} | {ws / 2**30:.2f} | "
-              f"{m.weight_bytes() / 2**20:.0f} |", file=sys.stderr)
+            best = float("inf")
+            for _ in range(3):
+                t0 = time.perf_counter()
+                m.forward(n, n, z, img, n=b)
+                torch.cuda.synchronize()
+                best = min(best, time.perf_counter() - t0)
+            if not bool(torch.isfinite(img).all().item()):
+                raise RuntimeError("non-finite image")
+            lat[b] = best
+            fl = b * decoder_flops(arch, n, n)
+            row = {"table": "decode", "decoder": args.decoder, "image": n * f, "latent": n, "batch": b, "ms": best * 1e3,
+                   "latency_vs_b1": best / lat[1], "images_per_s": b / best, "product_flops": fl, "tflops": fl / best / 1e12,
+                   "workspace_bytes": ws, "weight_bytes": m.weight_bytes()}
+            rows.append(row)
+            print(json.dumps(row), flush=True)
+            del z, img
+        print(json.dumps({"table": "decode_optimum", "decoder": args.decoder, "image": n * f, "optimal_batch": optimal_batch(lat),
+                          "rule": "largest B with latency < 1.2 x latency(B=1)"}), flush=True)
+    print("| image | latent | GFLOP/image | " + " | ".join(f"B={b}" for b in batches) + " | optimal B | workspace GiB (B=1) |", file=sys.stderr)
+    print("|" + "---|" * (len(batches) + 5), file=sys.stderr)
+    for n in sizes:
+        rr = {r["batch"]: r for r in rows if r["latent"] == n}
+        cells = " | ".join((f"{rr[b]['ms']:.2f} ms (x{rr[b]['latency_vs_b1']:.2f}, {rr[b]['tflops']:.0f} TF)" if b in rr else "-") for b in batches)
+        print(f"| {n * f}x{n * f} | {n}x{n} | {decoder_flops(arch, n, n) / 1e9:.0f} | {cells} | "
+              f"{optimal_batch({b: r['ms'] for b, r in rr.items()})} | {rr[1]['workspace_bytes'] / 2**30:.2f} |", file=sys.stderr)
+    print(f"weights {m.weight_bytes() / 2**20:.0f} MiB", file=sys.stderr)
 
 
 def run_pipeline(args):
@@ -350,11 +370,11 @@ def main():
     ap.add_argument("--max-batch", type=int, default=None)
     args = ap.parse_args()
     if args.max_batch is None:
-        args.max_batch = 64 if args.table == "encode" else 32
+        args.max_batch = 64 if args.table == "encode" else 8 if args.table == "decode" else 32
     if args.table == "encode":
         return run_encode(args)
     if args.table == "decode":
-        args.res = args.res or "256,512,1024"
+        args.res = args.res or "128,256,512,1024"
         return run_decode(args)
     if args.table == "pipeline":
         args.res = args.res or "512,1024"

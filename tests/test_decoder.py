@@ -223,6 +223,47 @@ def test_decoder_last_layer_as_a_product_when_the_last_level_is_wide(torch, X):
 
 
 @pytest.mark.gpu
+def test_decoder_batch_of_same_size_latents(torch, X):
+    """Three latents in one call: each image against the oracle, captured streams stacked image
+    after image, and an image's result bit-identical whatever its batch mates are."""
+    params = _params(ARCH)
+    h = w = 16                                   # 256 latent pixels: the batch form's granularity
+    zs = [_latent(ARCH, h, w, seed=10 + i) for i in range(3)]
+    m = X.Decoder(ARCH)
+    m.ensure_workspace(h, w, 3)
+    m.init_weights(0, 0.0)
+    m.set_params(params)
+    f = m.up_factor()
+    top = torch.zeros((3 * h * w * 4 ** 3, ARCH["channels"][3]), dtype=torch.float32, device="cuda")
+    mid = torch.zeros((3 * h * w, ARCH["channels"][0]), dtype=torch.float32, device="cuda")
+    m.set_tap("up3", top)
+    m.set_tap("mid.attn", mid)
+
+    def run(order):
+        z = torch.from_numpy(np.stack([zs[i] for i in order])).cuda()
+        img = torch.full((3, h * f, w * f, 3), float("nan"), dtype=torch.float32, device="cuda")
+        m.forward(h, w, z, img, n=3)
+        torch.cuda.synchronize()
+        return img.cpu().numpy()
+
+    got = run([0, 1, 2])
+    tops, mids = top.cpu().numpy().reshape(3, -1, ARCH["channels"][3]), mid.cpu().numpy().reshape(3, -1, ARCH["channels"][0])
+    ora = D.DecoderOracle(ARCH, params)
+    for i in range(3):
+        taps = {}
+        ref = ora.forward(np.transpose(zs[i], (1, 2, 0)), taps)
+        _check_image(got[i], ref)
+        assert rel_l2(mids[i], taps["mid.attn"].reshape(mids[i].shape)) <= 1e-2
+        assert rel_l2(tops[i], taps["up3"].reshape(tops[i].shape)) <= 2e-2
+    m.clear_taps()
+    other = run([0, 2, 1])
+    assert np.array_equal(other[0], got[0]) and np.array_equal(other[1], got[2]) and np.array_equal(other[2], got[1])
+    # sizes the batch form does not take
+    assert m.workspace_bytes(8, 8, 2) == 0 and m.workspace_bytes(16, 16, 65) == 0 and m.workspace_bytes(16, 16, 0) == 0
+    m.close()
+
+
+@pytest.mark.gpu
 def test_decoder_smaller_call_after_a_larger_one_is_unaffected(torch, X):
     """The workspace is reused with other image sizes: zero borders and padded channels must not
     carry over.  Same context, large then small latent, against a fresh context."""
