@@ -450,6 +450,31 @@ def test_tiny_config_sample_and_step_composition(torch):
     assert np.array_equal(case.gpu_sample()[0], final_gpu[0])
 
 
+def test_context_on_a_caller_stream_matches_the_default_stream(torch):
+    """A context created on the caller's HIP stream: every launch and copy of a call goes to that
+    stream (the call returns before the work is done), and the result is bit-identical to the
+    same call on the default stream."""
+    from paper_2510_02838_amd import binding as Bn
+    cfg = synth.CONFIGS["tiny"]
+    case = Case(torch, cfg["arch"], synth.make_requests("tiny"), cfg["steps"], std=0.06, bias_std=0.1)
+    want = case.gpu_sample()[0]
+    side = torch.cuda.Stream()
+    m = Bn.DiT(cfg["arch"], 0, stream=side.cuda_stream)
+    m.ensure_workspace(case.reqs, cfg["steps"])
+    m.init_weights(0, 0.0)
+    m.set_params(case.params)
+    x = case.dev_latents()
+    torch.cuda.synchronize()                     # inputs were produced on the default stream
+    busy = torch.randn(4096, 4096, device="cuda")
+    for _ in range(4):                           # unrelated work on the default stream meanwhile
+        busy = busy @ busy * 1e-3
+    m.sample(case.reqs, x, case.d_cond, case.sigmas)
+    side.synchronize()
+    assert np.array_equal(x.cpu().numpy().reshape(want.shape), want)
+    torch.cuda.synchronize()
+    m.close()
+
+
 def test_tiny_golden_file(torch):
     """The stored oracle samples (tests/golden/tiny_oracle.txt) against the GPU path."""
     import os
