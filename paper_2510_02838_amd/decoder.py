@@ -49,11 +49,11 @@ def make_config(arch):
 class Decoder:
     """One decoder instance; weights and workspace are torch tensors owned by this object."""
 
-    def __init__(self, arch, device=0, bind=True):
+    def __init__(self, arch, device=0, bind=True, stream=None):
         self.cfg = make_config(arch)
         self.arch = arch
         self.ctx = _vp()
-        st = dec_create(C.byref(self.cfg), device, None, C.byref(self.ctx))
+        st = dec_create(C.byref(self.cfg), device, stream, C.byref(self.ctx))    # stream: HIP stream handle or None (default stream)
         if st != DIT_OK:
             raise DitError(st, "dec_create rejected the configuration")
         self.device = device

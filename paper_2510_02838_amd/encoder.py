@@ -45,12 +45,12 @@ def _lens(lens):
 class Encoder:
     """One encoder instance; weights and workspace are torch tensors owned by this object."""
 
-    def __init__(self, arch, device=0, bind=True):
+    def __init__(self, arch, device=0, bind=True, stream=None):
         self.cfg = enc_config(arch["vocab"], arch["d_model"], arch["n_heads"], arch["head_dim"], arch["d_ff"],
                               arch["n_layers"])
         self.arch = arch
         self.ctx = _vp()
-        st = enc_create(C.byref(self.cfg), device, None, C.byref(self.ctx))
+        st = enc_create(C.byref(self.cfg), device, stream, C.byref(self.ctx))    # stream: HIP stream handle or None (default stream)
         if st != DIT_OK:
             raise DitError(st, "enc_create rejected the configuration")
         self.device = device

@@ -26,11 +26,15 @@ each for the stages before and after it:
 
     python -m paper_2510_02838_amd.stage_profile encode [--encoder t5_xxl] [--lens 32,128,500] [--max-batch 64]
     python -m paper_2510_02838_amd.stage_profile decode [--decoder ae_kl] [--res 128,256,512,1024] [--max-batch 8]
-    python -m paper_2510_02838_amd.stage_profile pipeline [--workload sd3|flux] [--res 512,1024] [--steps 28]
+    python -m paper_2510_02838_amd.stage_profile pipeline [--workload sd3|flux] [--res 512,1024] [--steps 28] [--overlap N]
 
   pipeline  one request through all three stages on this GPU, the output of each feeding the next
           (prompt tokens -> condition -> T denoising steps -> image): time per stage and its share
           of the request (the paper's stage-time breakdown: Diffuse dominates, Decode 15-30 %).
+          --overlap N: then N requests back to back with the three stages on three HIP streams,
+          request i's Decode and request i+2's Encode running beside request i+1's Diffuse
+          (events hand the condition and the latent from stream to stream), against the same N
+          requests stage after stage on one stream.
 
 Resolutions are pixels; a latent is res/8 on a side and a patch 2x2, so tokens = (res/16)^2
 plus the text tokens of the workload.  For the video family `--res` lists
@@ -64,7 +68,7 @@ def _tokens(arch, req):
 class Stage:
     """One model instance; workspace grows to the largest request list seen."""
 
-    def __init__(self, workload, steps):
+    def __init__(self, workload, steps, stream=None):
         import torch
         import synth
         from . import binding as B
@@ -73,7 +77,7 @@ class Stage:
         self.arch = self.cfg["arch"]
         self.n_cond = self.cfg["n_cond"]
         self.steps = steps
-        self.m = B.DiT(self.arch)
+        self.m = B.DiT(self.arch, 0, stream=stream)
         self.ready = False
 
     def prepare(self, all_req_lists):
@@ -347,6 +351,69 @@ def run_pipeline(args):
         print(json.dumps(row), flush=True)
         print(f"| {spec} | {row['tokens']} | {t_e * 1e3:.2f} | {t_d * 1e3:.1f} | {t_c * 1e3:.2f} | {tot * 1e3:.1f} | "
               f"{100 * t_e / tot:.1f} % / {100 * t_d / tot:.1f} % / {100 * t_c / tot:.1f} % |", file=sys.stderr)
+    if args.overlap:
+        _overlap(args, specs[-1], reqs[-1])
+
+
+def _overlap(args, spec, rq):
+    """N requests of one shape: the three stages on three streams against one stream."""
+    import torch
+    import synth
+    from . import encoder as XE, decoder as XD
+    N = args.overlap
+    enc_arch, dec_arch = synth.ENCODERS["t5_xxl"], synth.DECODERS["ae_kl"]
+    _, h, w, n_cond = rq[0]
+    results = {}
+    for mode in ("one stream", "three streams"):
+        streams = [torch.cuda.Stream() for _ in range(3)] if mode == "three streams" else [torch.cuda.Stream()] * 3
+        se, sd, sc = streams
+        st = Stage(args.workload, args.steps, stream=sd.cuda_stream)
+        st.prepare([rq])
+        arch = st.arch
+        enc = XE.Encoder(enc_arch, stream=se.cuda_stream)
+        enc.ensure_workspace([n_cond]); enc.init_weights(1, 0.02)
+        dec = XD.Decoder(dec_arch, stream=sc.cuda_stream)
+        dec.ensure_workspace(h, w); dec.init_weights(1, 0.02)
+        f = dec.up_factor()
+        toks = torch.from_numpy(np.concatenate(synth.make_tokens([n_cond], enc_arch["vocab"]))).cuda()
+        sg = np.stack([synth.default_sigmas(args.steps, 1.0)])
+        x0 = torch.from_numpy(synth.gaussian(2, "latent", arch["latent_ch"] * h * w).astype(np.float32)).cuda()
+        # per-request buffers: a stage may run ahead of the next one
+        conds = [torch.empty((n_cond, arch["cond_dim"]), dtype=torch.bfloat16, device="cuda") for _ in range(N)]
+        xs = [x0.clone() for _ in range(N)]
+        imgs = [torch.empty((h * f, w * f, dec_arch["out_ch"]), dtype=torch.float32, device="cuda") for _ in range(2)]
+        torch.cuda.synchronize()
+
+        def run():
+            ev_e = [torch.cuda.Event() for _ in range(N)]
+            ev_d = [torch.cuda.Event() for _ in range(N)]
+            for i in range(N):
+                enc.forward([n_cond], toks, conds[i], None)
+                ev_e[i].record(se)
+            for i in range(N):
+                sd.wait_event(ev_e[i])
+                st.m.sample(rq, xs[i], conds[i], sg)
+                ev_d[i].record(sd)
+                sc.wait_event(ev_d[i])
+                dec.forward(h, w, xs[i], imgs[i % 2])
+            torch.cuda.synchronize()
+
+        run()                                          # warm-up
+        for x in xs:
+            x.copy_(x0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run()
+        results[mode] = time.perf_counter() - t0
+        if not bool(torch.isfinite(imgs[(N - 1) % 2]).all().item()):
+            raise RuntimeError("non-finite image")
+        del st, enc, dec
+    row = {"table": "pipeline_overlap", "workload": args.workload, "image": spec, "requests": N,
+           "one_stream_ms": results["one stream"] * 1e3, "three_streams_ms": results["three streams"] * 1e3,
+           "requests_per_s_one": N / results["one stream"], "requests_per_s_three": N / results["three streams"]}
+    print(json.dumps(row), flush=True)
+    print(f"{N} requests of {spec}: one stream {results['one stream'] * 1e3:.1f} ms, three streams {results['three streams'] * 1e3:.1f} ms "
+          f"({results['one stream'] / results['three streams']:.3f}x)", file=sys.stderr)
 
 
 DEFAULT_RES = {
@@ -368,6 +435,7 @@ def main():
     ap.add_argument("--res", default=None)
     ap.add_argument("--steps", type=int, default=None, help="denoising steps per timed sample")
     ap.add_argument("--max-batch", type=int, default=None)
+    ap.add_argument("--overlap", type=int, default=0, help="pipeline: also run N requests with the stages on three streams")
     args = ap.parse_args()
     if args.max_batch is None:
         args.max_batch = 64 if args.table == "encode" else 8 if args.table == "decode" else 32
