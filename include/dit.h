@@ -209,6 +209,23 @@ dit_status dit_op_gemm_splitk(void* stream, const void* A, int lda, const void* 
                               int ldc, const float* gate, int gate_stride, const int* row_req,
                               int splits, void* work, size_t work_bytes);
 
+/* dit_op_gemm_splitk for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same kernels and the
+ * same result bit for bit, with the partial tiles kept in an array inside the library's own
+ * device image instead of a caller-supplied `work` buffer.  The call allocates and frees
+ * nothing.  Limit: ceil(M/128)*ceil(N/128)*splits*65536 <= DIT_STATIC_SCRATCH_BYTES (16 MiB,
+ * i.e. 256 partial tiles; each GPU the library runs on holds this array until the process
+ * ends); larger products return DIT_ENOMEM before anything is launched.  The array belongs to
+ * the device that is current at the call and is shared by every call on that device: calls
+ * that overlap on one GPU (different streams, different threads) race on it and must be
+ * serialised by the caller.  Nothing in it needs clearing between calls: each call's product
+ * kernel writes every partial tile its reduction reads. */
+#define DIT_STATIC_SCRATCH_BYTES (16u << 20)
+dit_status dit_op_gemm_splitk_static(void* stream, const void* A, int lda, const void* W, int ldw,
+                                     const float* bias, int M, int N, int K, int out_kind,
+                                     void* out, int ldc, const float* gate, int gate_stride,
+                                     const int* row_req, int splits);
+
 /* Flash-style attention over packed segments: softmax(Q K^T / sqrt(dh)) V per segment and
  * head, no other mask.  q: dev bf16 rows [Nq][H*dh] with row stride ldq (elements); k likewise
  * [Nk] rows; vt: dev bf16 [H][dh][ldvt], the transposed values, segment s occupying columns

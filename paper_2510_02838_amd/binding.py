@@ -62,6 +62,7 @@ _SIGS = {
     "dit_op_gemm_qknorm": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _i, _i, _vp, _i, _i, _i, _i, _vp, _vp, _vp, _vp, _vp, _vp,
                                 _i, C.c_float]),
     "dit_op_gemm_splitk": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _i, _vp, _sz]),
+    "dit_op_gemm_splitk_static": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _i, _i, _i, _vp, _i, _vp, _i, _vp, _i]),
     "dit_op_gemm_variant": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _i, _i, _i, _vp, _i, _i]),
     "dit_op_attention_work_bytes": (_sz, [_i, _ip]),
     "dit_op_attention": (_i, [_vp, _vp, _i, _vp, _i, _vp, _i, _vp, _i, _i, _i, _i, _ip, _ip, _ip, _vp, _sz, _i, C.c_float]),

@@ -856,6 +856,15 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
 
 }  // namespace
 
+// Split-K scratch that lives in the library's own device image, for callers that may not
+// allocate: one array per GPU the library runs on (every device loads its own copy of the
+// code object), held until the process ends.  The name below is a host-side stand-in; the
+// device address is looked up once per device and only that pointer is ever handed to
+// kernels.
+static __device__ __align__(256) unsigned char scratch[DIT_STATIC_SCRATCH_BYTES];
+static std::atomic<unsigned char*> scratch_ptr[32];    // per device: address of its copy
+
+
 // =======================================================================================
 // C ABI
 // =======================================================================================
@@ -1124,6 +1133,35 @@ dit_status dit_op_gemm_splitk(void* stream, const void* A, int lda, const void* 
   GemmBatch b; b.n = 1; b.total_tiles = 0;
   b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc, gate, gate_stride, row_req);
   b.splits = splits; b.partial = (float*)work; b.partial_bytes = work_bytes;
+  launch_gemm((hipStream_t)stream, b, 40128128);
+  return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
+}
+
+dit_status dit_op_gemm_splitk_static(void* stream, const void* A, int lda, const void* W, int ldw, const float* bias,
+                                     int M, int N, int K, int out_kind, void* out, int ldc, const float* gate,
+                                     int gate_stride, const int* row_req, int splits) {
+  if (!A || !W || !out) return DIT_EINVAL;
+  if (M <= 0 || N <= 0 || K <= 0 || K % 64 || lda < K || ldw < K || ldc < N) return DIT_ESHAPE;
+  if (lda % 8 || ldw % 8) return DIT_ESHAPE;
+  if (out_kind < 0 || out_kind > 3) return DIT_EINVAL;
+  if (ldc % ((out_kind == 1 || out_kind == 3) ? 4 : 8) || ((uintptr_t)out & 15)) return DIT_ESHAPE;
+  if (splits < 1 || splits > K / 64) return DIT_ESHAPE;
+  const size_t tiles = (size_t)((M + 127) / 128) * ((N + 127) / 128);
+  if (tiles * splits * (128 * 128 * 4) > (size_t)DIT_STATIC_SCRATCH_BYTES) return DIT_ENOMEM;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 32) return DIT_EDEVICE;
+  unsigned char* ptr = scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!ptr) {      // first call on this device (it is the current one): where its copy of the array lives
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return DIT_EDEVICE;
+    ptr = (unsigned char*)p;
+    scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
+  GemmBatch b; b.n = 1; b.total_tiles = 0;
+  b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc, gate, gate_stride, row_req);
+  // every partial tile the reduction reads is written in full by the product kernel of the
+  // same call, so nothing of the previous call's contents has to be cleared
+  b.splits = splits; b.partial = (float*)ptr; b.partial_bytes = DIT_STATIC_SCRATCH_BYTES;
   launch_gemm((hipStream_t)stream, b, 40128128);
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }
