@@ -13,9 +13,13 @@
  *  - "dev" pointers are device (HBM) addresses on the device given to dit_create; "host"
  *    pointers are ordinary host memory.  The library never allocates or frees device
  *    memory: weights, workspace, latents and conditions are the caller's buffers.
- *  - All GPU work is enqueued on the HIP stream given to dit_create (or dit_set_stream)
- *    and the calls do not synchronise, except dit_get_tensor / dit_set_tensor /
- *    dit_profile_read, which block until their copies are done.
+ *  - All GPU work is enqueued on the HIP stream given to dit_create (or dit_set_stream).
+ *    dit_get_tensor / dit_set_tensor / dit_profile_read block until their copies are done.
+ *    dit_denoise_step and dit_sample return without waiting for the GPU, with one exception:
+ *    the FIRST of them after dit_bind, dit_init_weights or dit_set_tensor waits for the
+ *    stream and reads the q/k norm gains back (a few KB, see dit_bind) before it launches.
+ *    The dit_op_* calls stage their small host arrays with hipMemcpyAsync from pageable
+ *    memory, which returns only after the host data has been read.
  *  - Every call returns a dit_status; arguments are validated before anything is
  *    launched, so a failing call leaves the caller's buffers untouched.  The text of the
  *    last error is kept per context (dit_last_error).  Nothing aborts or throws.
@@ -64,7 +68,14 @@ typedef struct {
   int cond_dim;               /* width of the condition tokens, multiple of 64           */
   int rope_axes[3];           /* rotary widths for (frame,row,col); all 0 = no rotary    */
   float rope_theta;
+  int act_dtype;              /* DIT_ACT_*: storage type of activations between kernels  */
 } dit_config;
+
+/* Activation storage.  Only bf16 is built: GEMM and attention operands are bf16 MFMA inputs,
+ * while accumulators, softmax and norm statistics, the residual stream, the model output and
+ * the latent are float32 in either mode.  dit_create returns DIT_EUNSUPPORTED for
+ * DIT_ACT_F32 (an all-float32 debug mode of the smallest benchmark configuration). */
+enum { DIT_ACT_F32 = 0, DIT_ACT_BF16 = 1 };
 
 /* One request: latent extent in LATENT units and number of condition tokens. */
 typedef struct { int frames, height, width, n_cond; } dit_req;

@@ -28,7 +28,7 @@ class dit_config(C.Structure):
     _fields_ = [("family", C.c_int), ("n_blocks", C.c_int), ("n_single", C.c_int), ("hidden", C.c_int),
                 ("n_heads", C.c_int), ("head_dim", C.c_int), ("mlp_hidden", C.c_int), ("latent_ch", C.c_int),
                 ("patch_t", C.c_int), ("patch_h", C.c_int), ("patch_w", C.c_int), ("cond_dim", C.c_int),
-                ("rope_axes", C.c_int * 3), ("rope_theta", C.c_float)]
+                ("rope_axes", C.c_int * 3), ("rope_theta", C.c_float), ("act_dtype", C.c_int)]
 
 
 class dit_req(C.Structure):
@@ -93,6 +93,7 @@ def make_config(arch):
     for a in range(3):
         cfg.rope_axes[a] = arch["rope_axes"][a]
     cfg.rope_theta = arch["rope_theta"]
+    cfg.act_dtype = {"f32": 0, "bf16": 1}[arch.get("act_dtype", "bf16")]
     return cfg
 
 

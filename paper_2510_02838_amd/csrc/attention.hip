@@ -29,6 +29,7 @@ namespace dit {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
@@ -76,6 +77,10 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 // 50 of the ~125 vector instructions per key tile, which on this machine add to, rather than
 // hide under, the matrix instructions.  (q/k RMS-normalised per head, as in all three block
 // families, gives |q.k| log2(e)/sqrt(dh) <= 1.44 sqrt(dh) |g_q| |g_k|: 11.5 or 16.3 for unit gains.)
+// MODE 4 (cross-attention to a short condition, whose output enters the residual stream without a
+// gate): as mode 1, with q and k stored as fp16 (both are RMS-normalised, hence bounded; three more
+// mantissa bits in the scores) and the values as two bf16 terms, V = vt + vt_lo, both multiplied by
+// the same probabilities: the rounding of k and v no longer shows in the output.
 template <int DH, int NW, int MODE>
 __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const AttnArgs a) {
   constexpr int NT = NW * 64;
@@ -90,6 +95,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
   extern __shared__ __attribute__((aligned(128))) unsigned char smem[];
   unsigned char* const sKb = smem;                   // two K tiles
   unsigned char* const sVb = smem + 2 * KBYTES;      // two V^T tiles
+  unsigned char* const sVlo = smem + 2 * KBYTES + 2 * VBYTES;   // MODE 4: two tiles of the values' second term
 
   // ---- which (tile, head) ------------------------------------------------------------
   int bid = blockIdx.x;
@@ -147,6 +153,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
 #pragma unroll
     for (int i = 0; i < LV; ++i)
       __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + gv[i]), (lptr_t)(dst + (i * NT + wave * 64) * 16), 16, 0, 0);
+    if constexpr (MODE == 4) {
+      unsigned char* dlo = sVlo + (kt & 1) * VBYTES;
+      const bf16_t* vlo = a.vt_lo + kt * KT;
+#pragma unroll
+      for (int i = 0; i < LV; ++i)
+        __builtin_amdgcn_global_load_lds((gptr_t)(vlo + gv[i]), (lptr_t)(dlo + (i * NT + wave * 64) * 16), 16, 0, 0);
+    }
   };
 
   // ---- LDS read offsets ------------------------------------------------------------------
@@ -169,7 +182,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
 #pragma unroll
       for (int t = 0; t < 2; ++t) {
         bf16x8 kf = *(const bf16x8*)(sK + t * 32 * KROW + ((c ^ kkey0) << 4));
-        st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
+        if constexpr (MODE == 4)       // the same 16-bit containers hold fp16 values
+          st[t] = __builtin_amdgcn_mfma_f32_32x32x16_f16(*(const f16x8*)&kf, *(const f16x8*)&qf[kk], st[t], 0, 0, 0);
+        else
+          st[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], st[t], 0, 0, 0);
       }
     }
     if constexpr (MODE == 3) {
@@ -222,6 +238,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
   // with the two register sets swapped on alternate tiles instead of copying sn to sc.
   auto step = [&](int kt, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
     const float c2 = (MODE == 0 || MODE == 3) ? c2_arg : 1.0f;
+    constexpr bool PRESCALED = MODE == 1 || MODE == 4;
     // ---- (A) raise the running max only when a row's tile max exceeds it by more than 2^8
     // in the exponent (softmax is shift-invariant, so a stale max is exact as long as nothing
     // overflows: probabilities stay below 2^8); this skips the rescale of O on most tiles.
@@ -254,8 +271,8 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int e = 0; e < 16; e += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(MODE == 2 ? sc[t][e] : MODE == 1 ? sc[t][e] - mc : sc[t][e] * c2 - mc);
-        const float p1 = __builtin_amdgcn_exp2f(MODE == 2 ? sc[t][e + 1] : MODE == 1 ? sc[t][e + 1] - mc : sc[t][e + 1] * c2 - mc);
+        const float p0 = __builtin_amdgcn_exp2f(MODE == 2 ? sc[t][e] : PRESCALED ? sc[t][e] - mc : sc[t][e] * c2 - mc);
+        const float p1 = __builtin_amdgcn_exp2f(MODE == 2 ? sc[t][e + 1] : PRESCALED ? sc[t][e + 1] - mc : sc[t][e + 1] * c2 - mc);
         const uint32_t w = pack2bf(p0, p1);
         pk[t][e >> 1] = w;
         l_run = __builtin_amdgcn_fdot2_f32_bf16(*(const bf16x2*)&w, ones, l_run, false);  // sum of the rounded values
@@ -272,6 +289,10 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
       for (int d = 0; d < ND; ++d) {
         bf16x8 vf = *(const bf16x8*)(sV + d * 32 * 128 + ((c ^ vkey) << 4));
         o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf.v, o[d], 0, 0, 0);
+        if constexpr (MODE == 4) {
+          bf16x8 vl = *(const bf16x8*)(sVlo + (kt & 1) * VBYTES + voff + d * 32 * 128 + ((c ^ vkey) << 4));
+          o[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vl, pf.v, o[d], 0, 0, 0);
+        }
       }
     }
     if constexpr (MODE != 2) mx = row_max(sn);
@@ -319,7 +340,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
 
 template <int DH, int NW, int MODE>
 static void launch_t(hipStream_t s, const AttnArgs& a) {
-  constexpr int lds = 2 * (KT * DH * 2 + DH * 128);   // two K tiles + two V^T tiles
+  constexpr int lds = 2 * (KT * DH * 2 + DH * 128) + (MODE == 4 ? 2 * DH * 128 : 0);   // two K tiles + two V^T tiles (+ two of the second term)
   auto kern = attn_kernel<DH, NW, MODE>;
   static std::atomic<unsigned> seen{0};
   if (first_use_on_device(seen))
@@ -338,6 +359,7 @@ void launch_attention(hipStream_t s, const AttnArgs& a) {
   if (a.mode == 3) {       // encoder attention: sequences are short, 128-query tiles only
     if (d64) launch_t<64, 4, 3>(s, a); else launch_t<128, 4, 3>(s, a);
   }
+  else if (a.mode == 4) ATTN_DISPATCH(4);
   else if (a.mode == 2) ATTN_DISPATCH(2);
   else if (a.mode == 1) ATTN_DISPATCH(1);
   else ATTN_DISPATCH(0);

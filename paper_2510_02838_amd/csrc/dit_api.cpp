@@ -65,7 +65,7 @@ struct Plan {
 };
 
 struct WsLayout {
-  size_t meta, sig, coef_a, coef_b, feat, th1, vec, mhi, mlo, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, o, act, cproj,
+  size_t meta, sig, coef_a, coef_b, feat, th1, vec, mhi, mlo, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, vtlo, o, act, cproj,
       patch, yfin, rope, partial, total;
   int MC = 0;        // modulation columns per conditioning row
   int R = 0;         // conditioning rows = steps * n_req
@@ -361,15 +361,16 @@ void layout_ws(const dit_ctx* c, const Plan& P, int max_steps, WsLayout& L) {
   L.modblk = take((size_t)P.n_req * 6 * d * 4);
   L.x = take(Ns * d * 4);
   L.xj = take(g.family == DIT_FAMILY_F ? Nj * d * 4 : 0);
-  L.xt0 = take(P.has_txt_stream ? Nt * d * 4 : 0);
+  L.xt0 = take(Nt * d * 4);                      // projected condition, fp32
   L.h = take(std::max(Ns, Nj) * d * 2);
   L.qkv = take(std::max(Ns, Nj) * 3 * d * 2);
   L.q = take(Nj * d * 2);
   L.k = take(std::max(Nj, Nt) * d * 2);
   L.vt = take(d * (size_t)std::max(P.Nv_pad, P.Nvx_pad) * 2);
+  L.vtlo = take(g.family == DIT_FAMILY_W ? d * (size_t)P.Nvx_pad * 2 : 0);   // cross-attention values, second term
   L.o = take(Ns * d * 2);
-  L.act = take(std::max(Ns * dff, std::max(Nj * wide, Nt * 2 * d)) * 2);
-  L.cproj = take(g.family == DIT_FAMILY_W ? Nt * d * 2 : 0);
+  L.act = take(std::max(std::max(Ns * dff, Nj * wide) * 2, Nt * 2 * d * 4));    // (family W: fp32 keys|values of the condition)
+  L.cproj = take(g.family == DIT_FAMILY_W ? Nt * d * 2 * 2 : 0);               // projected condition as two bf16 terms
   L.patch = take(Ni * (size_t)L.ldp * 2 * 2);   // hi and lo terms
   L.yfin = take(Ni * (size_t)L.ldy * 4);
   L.rope = take((g.rope_axes[0] + g.rope_axes[1] + g.rope_axes[2]) > 0 ? Nj * (g.head_dim / 2) * 8 : 0);
@@ -472,7 +473,7 @@ static float gmax(const dit_ctx* c, const std::string& a, const std::string& b =
 void run_attention(dit_ctx* c, const Run& R, const bf16_t* q, int ldq, const bf16_t* k, int ldk, const bf16_t* vt,
                    int ldvt, bf16_t* o, int ldo, const int* cu_q, const int* cu_k, const int* vt_off,
                    const AttnTile* tiles, int n_tiles, const int* o_row_map, double flop_units,
-                   float q_gain_max, float k_gain_max) {
+                   float q_gain_max, float k_gain_max, const bf16_t* vt_lo = nullptr) {
   const dit_config& g = c->cfg;
   AttnArgs a;
   a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.ldvt = ldvt; a.o = o; a.ldo = ldo;
@@ -484,6 +485,7 @@ void run_attention(dit_ctx* c, const Run& R, const bf16_t* q, int ldq, const bf1
   // attention kernel needs no running max.
   const float logit_bound = a.scale_log2 * (float)g.head_dim * q_gain_max * k_gain_max * 1.02f;
   a.mode = logit_bound <= 60.0f ? 2 : 1;
+  if (vt_lo) { a.mode = 4; a.vt_lo = vt_lo; }    // fp16 q/k, two-term values, running max
   Scope sc(c, DIT_PROF_ATTN, flop_units * g.hidden, 0);
   launch_attention(c->stream, a);
 }
@@ -630,26 +632,29 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
     Scope sc(c, DIT_PROF_LNMOD, 0, 6.0 * Ni * d);
     launch_ln_modulate(c->stream, x, h, Ni, d, nullptr, nullptr, 0, nullptr, Wv(c, p + ".xnorm.g"), Wv(c, p + ".xnorm.b"));
   }
-  GemmProblem pxq = mk(h, d, Wm(c, p + ".xq.w"), Wld(c, p + ".xq.w"), Wv(c, p + ".xq.b"), Ni, d, d, OUT_BF16, qkv, d);
-  GemmProblem pxkv = mk(cproj, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), Wv(c, p + ".xkv.b"), Nt, 2 * d, d, OUT_BF16, act, 2 * d);
-  if (fuse) {     // queries only / keys then plain values
-    pxq = with_qknorm(pxq, d, 0, g.head_dim, Wv(c, p + ".xqnorm.g"), nullptr, nullptr, nullptr, q, nullptr, d, qs);
-    pxkv = with_qknorm(pxkv, 0, d, g.head_dim, nullptr, Wv(c, p + ".xknorm.g"), nullptr, nullptr, nullptr, k, d, 1.f);
-  }
-  run_gemm(c, {pxq, pxkv});
+  // The cross-attention output enters the residual stream without a gate, so its rounding noise is
+  // not damped as that of the gated branches is: queries and keys are stored as fp16 (both are
+  // RMS-normalised, hence bounded), the condition's keys and values are formed from the two-term
+  // projected condition with fp32 results, and the values go to the attention as two bf16 terms.
+  // (Always the product's epilogue: there is no capture point between it and the attention.)
+  if (!(gmax(c, p + ".xqnorm.g") <= 1024.f && gmax(c, p + ".xknorm.g") <= 1024.f))
+    return fail(c, DIT_EUNSUPPORTED, "%s: cross-attention norm gains above 1024 do not fit the fp16 storage of its queries and keys", p.c_str());
+  GemmProblem pxq = with_qknorm(mk(h, d, Wm(c, p + ".xq.w"), Wld(c, p + ".xq.w"), Wv(c, p + ".xq.b"), Ni, d, d, OUT_BF16, qkv, d),
+                                d, 0, g.head_dim, Wv(c, p + ".xqnorm.g"), nullptr, nullptr, nullptr, q, nullptr, d, qs);
+  pxq.qk.f16 = 1;
+  float* kv32 = R.at<float>(L.act);
+  bf16_t* cproj_lo = cproj + (size_t)Nt * d;
+  bf16_t* vtlo = R.at<bf16_t>(L.vtlo);
+  run_gemm(c, {pxq, mk(cproj, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), Wv(c, p + ".xkv.b"), Nt, 2 * d, d, OUT_F32, kv32, 2 * d)});
+  run_gemm(c, {mk(cproj_lo, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), nullptr, Nt, 2 * d, d, OUT_RESID_F32, kv32, 2 * d)});
   {
-    Scope sc(c, DIT_PROF_QKNORM, 0, fuse ? 4.0 * Nt * d : 4.0 * Ni * d + 8.0 * Nt * d);
-    if (!fuse) {
-      launch_qknorm_rope(c->stream, qkv, d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".xqnorm.g"), nullptr, nullptr, nullptr, q, nullptr, d, 0, 0,
-                         -1, nullptr, nullptr, qs);
-      launch_qknorm_rope(c->stream, act, 2 * d, Nt, g.n_heads, g.head_dim, Wv(c, p + ".xknorm.g"), nullptr, nullptr, nullptr, k, nullptr, d, 0, 0,
-                         -1, nullptr, nullptr, 1.f);
-    }
-    launch_v_transpose(c->stream, act, 2 * d, d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col_x), P.Nvx_pad, vt, P.Nvx_pad);
+    Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Nt * d);
+    launch_cross_kv_finish(c->stream, kv32, 2 * d, Nt, g.n_heads, g.head_dim, Wv(c, p + ".xknorm.g"), k, d,
+                           R.ip(P.o_src_of_col_x), P.Nvx_pad, vt, vtlo, P.Nvx_pad);
   }
   run_attention(c, R, q, d, k, d, vt, P.Nvx_pad, o, d, R.ip(P.o_cu_img), R.ip(P.o_cu_txt), R.ip(P.o_vtx_off),
                 (const AttnTile*)(R.ws + L.meta + P.o_xtiles), (int)P.xtiles.size(), nullptr, P.xattn_flop,
-                gmax(c, p + ".xqnorm.g"), gmax(c, p + ".xknorm.g"));
+                gmax(c, p + ".xqnorm.g"), gmax(c, p + ".xknorm.g"), vtlo);
   TAP(p + ".xattn", o, Ni, d, 2, d);
   run_gemm(c, {mk(o, d, Wm(c, p + ".xproj.w"), Wld(c, p + ".xproj.w"), Wv(c, p + ".xproj.b"), Ni, d, d, OUT_RESID_F32, x, d)});
   TAP(p + ".x_cross", x, Ni, d, 4, d);
@@ -781,10 +786,11 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
       launch_rope_table(s, tok, R.ip(P.o_tok_of_row), P.Nj, g.head_dim, g.rope_axes[0], g.rope_axes[1], g.rope_axes[2], g.rope_theta, R.at<float2>(L.rope));
   }
   // condition projection
-  if (P.has_txt_stream)
-    run_gemm(c, {mk((const bf16_t*)cond, g.cond_dim, Wm(c, "c_embed.w"), Wld(c, "c_embed.w"), Wv(c, "c_embed.b"), Nt, d, g.cond_dim, OUT_F32, R.at<float>(L.xt0), d)});
-  else
-    run_gemm(c, {mk((const bf16_t*)cond, g.cond_dim, Wm(c, "c_embed.w"), Wld(c, "c_embed.w"), Wv(c, "c_embed.b"), Nt, d, g.cond_dim, OUT_BF16, R.at<bf16_t>(L.cproj), d)});
+  run_gemm(c, {mk((const bf16_t*)cond, g.cond_dim, Wm(c, "c_embed.w"), Wld(c, "c_embed.w"), Wv(c, "c_embed.b"), Nt, d, g.cond_dim, OUT_F32, R.at<float>(L.xt0), d)});
+  if (!P.has_txt_stream) {      // family W: the cross-attention reads it as two bf16 terms
+    Scope sc(c, DIT_PROF_OTHER, 0, 0);
+    launch_silu_split(s, R.at<float>(L.xt0), R.at<bf16_t>(L.cproj), R.at<bf16_t>(L.cproj) + (size_t)Nt * d, (long long)Nt * d, 0);
+  }
 
   const int soff_img = P.has_txt_stream ? Nt : 0;
   float* x_img = x + (size_t)soff_img * d;
@@ -887,6 +893,8 @@ dit_status dit_create(const dit_config* cfg, int device, void* hip_stream, dit_c
   if (rs != 0 && rs != g.head_dim) return DIT_ESHAPE;
   if (rs != 0 && !(g.rope_theta > 1.0f)) return DIT_EINVAL;
   if (g.family == DIT_FAMILY_J && rs != 0) return DIT_EUNSUPPORTED;
+  if (g.act_dtype != DIT_ACT_F32 && g.act_dtype != DIT_ACT_BF16) return DIT_EINVAL;
+  if (g.act_dtype == DIT_ACT_F32) return DIT_EUNSUPPORTED;      // only bf16 activation storage is built
   if ((long long)g.latent_ch * g.patch_t * g.patch_h * g.patch_w > 1024) return DIT_ESHAPE;
   dit_ctx* c = new (std::nothrow) dit_ctx();
   if (!c) return DIT_ENOMEM;

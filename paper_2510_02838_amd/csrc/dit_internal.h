@@ -32,6 +32,7 @@ struct QkNorm {
   const int* dst_row;                       // [M] or null
   bf16_t* qo; bf16_t* ko; int ldo;
   float qscale;
+  int f16 = 0;                              // store q / k as fp16 instead of bf16
 };
 
 struct GemmProblem {
@@ -83,8 +84,10 @@ struct AttnArgs {
   int mode;                     // 0: q unscaled, running max; 1: q rows carry scale_log2, running max;
                                 // 2: as 1 and |q.k| <= 60 for every pair: no running max at all;
                                 // 3: as 0 plus bias[head][key - query + bias_L - 1] added to the scores
+                                // 4: as 1 with q and k stored as fp16 and the values as two bf16 terms vt + vt_lo
   const float* bias = nullptr;  // mode 3: dev [n_heads][2*bias_L - 1]
   int bias_L = 0;               // mode 3: no segment is longer than this
+  const bf16_t* vt_lo = nullptr; // mode 4: second term of the transposed values, same layout as vt
 };
 void launch_attention(hipStream_t s, const AttnArgs& a);
 
@@ -120,7 +123,12 @@ void launch_skinny(hipStream_t s, const float* x, int ldx, const bf16_t* W, int 
                    const float* bias, float* y, int ldy, int M, int N, int K, int silu_in);
 
 void launch_timestep_features(hipStream_t s, const float* sigma_dev, float* out, int M);
-void launch_silu_split(hipStream_t s, const float* x, bf16_t* hi, bf16_t* lo, long long n);
+void launch_silu_split(hipStream_t s, const float* x, bf16_t* hi, bf16_t* lo, long long n, int silu = 1);   // hi + lo = SiLU(x) or x
+// cross-attention keys (per-head RMS norm * gain, fp16) and transposed values (two bf16 terms) from
+// the fp32 product kv[M][ld] = [keys | values]; vt_*: [H][dh][ldvt], column c takes row src_of_col[c]
+void launch_cross_kv_finish(hipStream_t s, const float* kv, int ld, int M, int H, int dh, const float* kgain,
+                            bf16_t* k16, int ldk, const int* src_of_col, int n_cols_pad, bf16_t* vt_hi,
+                            bf16_t* vt_lo, int ldvt);
 
 // patchify: latents fp32 packed -> bf16 [n_img][ldp] (columns >= pdim zero)
 struct TokInfo { int req; int f, i, j; };  // per image token: request and grid position

@@ -272,19 +272,70 @@ void launch_skinny(hipStream_t s, const float* x, int ldx, const bf16_t* W, int 
   hipLaunchKernelGGL(skinny_kernel, dim3((N + 3) / 4), dim3(256), 0, s, x, ldx, W, ldw, bias, y, ldy, M, N, K, silu_in);
 }
 
-// hi + lo = SiLU(x) as two bf16 terms (about 16 mantissa bits), for feeding an MFMA GEMM
+// hi + lo = SiLU(x) (or x itself) as two bf16 terms (about 16 mantissa bits), for feeding an MFMA GEMM
 __global__ __launch_bounds__(256) void silu_split_kernel(const float* __restrict__ x, bf16_t* __restrict__ hi,
-                                                         bf16_t* __restrict__ lo, long long n) {
+                                                         bf16_t* __restrict__ lo, long long n, int silu) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   if (i >= n) return;
-  const float v = silu_f(x[i]);
+  const float v = silu ? silu_f(x[i]) : x[i];
   const uint16_t h = f2bf(v);
   hi[i] = h;
   lo[i] = f2bf(v - bf2f(h));
 }
-void launch_silu_split(hipStream_t s, const float* x, bf16_t* hi, bf16_t* lo, long long n) {
+void launch_silu_split(hipStream_t s, const float* x, bf16_t* hi, bf16_t* lo, long long n, int silu) {
   if (n == 0) return;
-  hipLaunchKernelGGL(silu_split_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, hi, lo, n);
+  hipLaunchKernelGGL(silu_split_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, x, hi, lo, n, silu);
+}
+
+// ---------------------------------------------------------------------------------------
+// Keys and values of a cross-attention from their fp32 product kv[rows][2d] (key columns, then
+// value columns).  Keys: per-head RMS norm (eps 1e-6) times gain, stored as fp16 (a normalised
+// key is bounded by sqrt(dh) max|gain|, far inside the fp16 range, and fp16 keeps three more
+// mantissa bits than bf16).  Values: transposed, as two bf16 terms hi + lo:
+// vt_*[h][c][col] = v[src_of_col[col]][h*dh + c]  (0 where src < 0).
+// ---------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void cross_k_norm_kernel(const float* __restrict__ kv, int ld, int M, int H, int dh,
+                                                           const float* __restrict__ gain, uint16_t* __restrict__ ko,
+                                                           int ldo) {
+  const int wave = (int)(((long long)blockIdx.x * 256 + threadIdx.x) >> 6), lane = threadIdx.x & 63;
+  if (wave >= M * H) return;
+  const int row = wave / H, h = wave - row * H;
+  const float* src = kv + (size_t)row * ld + h * dh;
+  const int per = dh >> 6;                      // 1 or 2 elements per lane
+  float x[2] = {0.f, 0.f}, ss = 0.f;
+  for (int e = 0; e < per; ++e) { x[e] = src[lane * per + e]; ss += x[e] * x[e]; }
+  ss = wave_sum(ss);
+  const float r = rsqrtf(ss / (float)dh + 1e-6f);
+  for (int e = 0; e < per; ++e) {
+    const _Float16 hv = (_Float16)(x[e] * r * gain[lane * per + e]);
+    ko[(size_t)row * ldo + h * dh + lane * per + e] = *(const uint16_t*)&hv;
+  }
+}
+__global__ __launch_bounds__(256) void cross_vt_split_kernel(const float* __restrict__ kv, int ld, int v_col_off, int dh,
+                                                             const int* __restrict__ src_of_col,
+                                                             bf16_t* __restrict__ vt_hi, bf16_t* __restrict__ vt_lo,
+                                                             int ldvt) {
+  const int c0 = blockIdx.x * 64, h = blockIdx.y;
+  const int col = threadIdx.x & 63, cg = threadIdx.x >> 6;
+  const int src = src_of_col[c0 + col];
+  for (int c = cg; c < dh; c += 4) {
+    const float v = src >= 0 ? kv[(size_t)src * ld + v_col_off + h * dh + c] : 0.f;
+    const uint16_t hi = f2bf(v);
+    const size_t o = ((size_t)h * dh + c) * ldvt + c0 + col;
+    vt_hi[o] = hi;
+    vt_lo[o] = f2bf(v - bf2f(hi));
+  }
+}
+void launch_cross_kv_finish(hipStream_t s, const float* kv, int ld, int M, int H, int dh, const float* kgain,
+                            bf16_t* k16, int ldk, const int* src_of_col, int n_cols_pad, bf16_t* vt_hi,
+                            bf16_t* vt_lo, int ldvt) {
+  if (M == 0) return;
+  const long long waves = (long long)M * H;
+  hipLaunchKernelGGL(cross_k_norm_kernel, dim3((unsigned)((waves + 3) / 4)), dim3(256), 0, s, kv, ld, M, H, dh, kgain,
+                     (uint16_t*)k16, ldk);
+  if (n_cols_pad > 0)
+    hipLaunchKernelGGL(cross_vt_split_kernel, dim3(n_cols_pad / 64, H), dim3(256), 0, s, kv, ld, H * dh, dh, src_of_col,
+                       vt_hi, vt_lo, ldvt);
 }
 
 // out[m][0..127] = cos(1000 sigma f_k), out[m][128..255] = sin(...), f_k = exp(-ln(1e4) k/128)

@@ -55,6 +55,14 @@ __device__ __forceinline__ uint32_t pack2bf(float a, float b) {
   return *(uint32_t*)&r;
 }
 
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+// two floats -> packed fp16 pair, round-to-nearest-even
+__device__ __forceinline__ uint32_t pack2h(float a, float b) {
+  f32x2 v = {a, b};
+  f16x2 r = __builtin_convertvector(v, f16x2);
+  return *(uint32_t*)&r;
+}
+
 __device__ __forceinline__ float gelu_tanh(float x) {
   // 0.5 x (1 + tanh(u)) == x * sigmoid(2u) == x / (1 + 2^(-2 log2(e) u)),
   // u = sqrt(2/pi) (x + 0.044715 x^3); hardware exp2 and reciprocal (1 ulp each)
@@ -110,11 +118,10 @@ __device__ __forceinline__ void tile_coords(const GemmProblem& P, int t, int& tm
   tn = r / gsz;
 }
 
-// MODE: 0 = production; 2 and 3 are measurement probes (global->LDS traffic only / LDS reads
-// + MFMAs only) whose output is meaningless; 4 = split-K: workgroup b = tile*splits + s walks
-// the s-th share of the k-slabs and leaves its fp32 accumulators, in register order, in chunk
-// b of batch.partial for splitk_reduce_kernel (small-M problems have too few tiles to fill
-// the chip and a lone tile's k-loop runs at global-memory latency per slab).
+// MODE: 0 = production; 4 = split-K: workgroup b = tile*splits + s walks the s-th share of the
+// k-slabs and leaves its fp32 accumulators, in register order, in chunk b of batch.partial for
+// splitk_reduce_kernel (small-M problems have too few tiles to fill the chip and a lone
+// tile's k-loop runs at global-memory latency per slab).
 // CONV: every problem of the batch is a 3x3 convolution (GemmProblem::conv_w > 0); a separate
 // instantiation so that the plain product's address arithmetic stays as it is.
 template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE, bool CONV = false>
@@ -243,34 +250,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     const unsigned char* cur = smem + st_cur * STAGE;
     const int st_nxt = st_cur + 1 == NS ? 0 : st_cur + 1;
     const unsigned char* nxt = smem + st_nxt * STAGE;
-    if (MODE != 2) {
-      load_frags(cur, 1, a1, b1);
+    load_frags(cur, 1, a1, b1);
+    mfma_all(a0, b0);
+    interleave_hint<TM + TN, TM * TN>();
+    if (KK == 4) {
+      load_frags(cur, 2, a0, b0);
+      mfma_all(a1, b1);
+      interleave_hint<TM + TN, TM * TN>();
+      load_frags(cur, 3, a1, b1);
       mfma_all(a0, b0);
       interleave_hint<TM + TN, TM * TN>();
-      if (KK == 4) {
-        load_frags(cur, 2, a0, b0);
-        mfma_all(a1, b1);
-        interleave_hint<TM + TN, TM * TN>();
-        load_frags(cur, 3, a1, b1);
-        mfma_all(a0, b0);
-        interleave_hint<TM + TN, TM * TN>();
-      }
     }
     // The last fragments of this slab are on their way to registers; slabs kt+1..kt+NS-1 are in
     // flight.  Wait for slab kt+1 (mine) and my fragments; after the barrier nobody reads `cur`
     // any more and `nxt` is visible to all.
-    if (MODE == 3) wait_vm<63, true>(); else wait_vm<(NS - 2) * LPS, true>();
+    wait_vm<(NS - 2) * LPS, true>();
     __syncthreads();
-    if (MODE != 3) issue(kt + NS);           // into the stage of slab kt
-    if (MODE != 2) {
-      load_frags(nxt, 0, a0, b0);            // (after the last slab this reads a stale stage; unused)
-      mfma_all(a1, b1);
-      interleave_hint<TM + TN, TM * TN>();
-    }
+    issue(kt + NS);                          // into the stage of slab kt
+    load_frags(nxt, 0, a0, b0);              // (after the last slab this reads a stale stage; unused)
+    mfma_all(a1, b1);
+    interleave_hint<TM + TN, TM * TN>();
     st_cur = st_nxt;
   }
   wait_vm<0, true>();                        // drain the redundant tail loads before LDS is released
-  if (MODE == 2) { load_frags(smem, 1, a1, b1); mfma_all(a1, b1); }
   if (MODE == 4) {
     // float4 number q = (((wave*TM + i)*TN + j)*4 + g)*64 + lane of the chunk holds
     // C[32i + 8g + 4*half + 0..3][32j + lane%32] of wave's sub-tile: 1 KB per store instruction
@@ -479,7 +481,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 #pragma unroll
           for (int pz = 0; pz < 4; ++pz) {
             const float a = v[it][2 * pz] * r * gv[2 * pz], b = v[it][2 * pz + 1] * r * gv[2 * pz + 1];
-            w[pz] = pack2bf(a * cs[2 * pz] - b * cs[2 * pz + 1], a * cs[2 * pz + 1] + b * cs[2 * pz]);
+            const float ra = a * cs[2 * pz] - b * cs[2 * pz + 1], rb = a * cs[2 * pz + 1] + b * cs[2 * pz];
+            w[pz] = Q.f16 ? pack2h(ra, rb) : pack2bf(ra, rb);
           }
           *(u32x4*)(dst + (size_t)drow * Q.ldo + col_in) = w;
         }
@@ -572,8 +575,6 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
 //   +1000000  8 waves (2x4) instead of 4 (2x2)
 //   +10000000 k-slab 32 with a 4-stage ring, +20000000 k-slab 32 with a 5-stage ring
 //             (default: k-slab 64, 2 stages)
-//   6256256 / 7256256  measurement probes on the 8-wave 256x256 k-slab-64 kernel,
-//   8256256 / 9256256  the same on the 4-wave one
 //   31256128 / 32256128 / 31128256  256x128 (4 waves / 8 waves) and 128x256 with a 3-stage ring
 //   30128128  128x128, k-slab 64, 4-stage ring (one workgroup per CU: for grids below 256 tiles)
 //   40128128  the same as split-K over b.splits shares of K plus the reduction kernel
@@ -636,8 +637,15 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     const long long rem = t256 % 256;
     tile = (t256 >= 1024 || (t256 >= 256 && (rem == 0 || rem >= 64))) ? 1256256 : 128128;
   }
-  bool conv = false, plain = false;
-  for (int i = 0; i < b.n; ++i) { conv = conv || b.p[i].conv_w > 0; plain = plain || b.p[i].conv_w <= 0; }
+  bool conv = false, plain = false, qknorm = false;
+  for (int i = 0; i < b.n; ++i) {
+    conv = conv || b.p[i].conv_w > 0; plain = plain || b.p[i].conv_w <= 0;
+    qknorm = qknorm || b.p[i].out_kind == OUT_QKNORM;
+  }
+  // the q/k-norm epilogue exists only in the instantiations whose waves own 64 output columns
+  if (qknorm && !(tile == 1256256 || tile == 11256256 || tile == 21256256 || tile == 128128 || tile == 10128128 ||
+                  tile == 30128128 || tile == 256128 || tile == 31256128 || tile == 32256128))
+    return -1;
   if (conv) {     // convolutions: never mixed with plain products, three tile shapes
     if (plain) return -1;
     for (int i = 0; i < b.n; ++i)        // whole images of whole rows
@@ -654,10 +662,6 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     case 11256256: launch_t<256, 256, 2, 4, 32, 4>(s, b); break;
     case 20256256: launch_t<256, 256, 2, 2, 32, 5>(s, b); break;
     case 21256256: launch_t<256, 256, 2, 4, 32, 5>(s, b); break;
-    case 6256256: launch_t<256, 256, 2, 4, 64, 2, 2>(s, b); break;
-    case 7256256: launch_t<256, 256, 2, 4, 64, 2, 3>(s, b); break;
-    case 8256256: launch_t<256, 256, 2, 2, 64, 2, 2>(s, b); break;
-    case 9256256: launch_t<256, 256, 2, 2, 64, 2, 3>(s, b); break;
     case 256128: launch_t<256, 128, 2, 2, 64, 2>(s, b); break;
     case 128256: launch_t<128, 256, 2, 2, 64, 2>(s, b); break;
     case 10128128: launch_t<128, 128, 2, 2, 32, 4>(s, b); break;

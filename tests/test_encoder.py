@@ -102,6 +102,32 @@ def test_encoder_forward_against_oracle(torch, X, lens):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("lens", [[32], [500, 7]])
+def test_encoder_benchmark_width_one_layer(torch, X, lens):
+    """The T5-XXL width the stage tables are timed at (d_model 4096, 64 heads, d_ff 10240), one
+    layer, vocabulary cut to 2048 rows (the lookup does not depend on the width of the table's
+    other dimension): three-product q/k/v launches, K = 10240 in the MLP's output product and, for
+    the short prompts, the split-K form, none of which the 256-wide test model reaches."""
+    arch = dict(synth.ENCODERS["t5_xxl"], n_layers=1, vocab=2048)
+    params, toks, m, d_tok = _case(torch, X, arch, lens, std=0.0125, bias_scale=2.0)
+    n = sum(lens)
+    out32 = torch.full((n, arch["d_model"]), float("nan"), dtype=torch.float32, device="cuda")
+    m.forward(lens, d_tok, None, out32)
+    torch.cuda.synchronize()
+    got32 = out32.cpu().numpy()
+    ora = E.EncoderOracle(arch, params)
+    o = 0
+    for s, L in enumerate(lens):
+        ref = ora.forward(toks[s])
+        g = got32[o:o + L]
+        assert np.isfinite(g).all()
+        assert max_abs(g, ref) <= 2e-2 * max(1.0, np.abs(ref).max()), (s, max_abs(g, ref))
+        assert rel_l2(g, ref) <= 1e-2, (s, rel_l2(g, ref))
+        o += L
+    m.close()
+
+
+@pytest.mark.gpu
 def test_encoder_intermediates_and_batch_independence(torch, X):
     lens = [40, 200]
     params, toks, m, d_tok = _case(torch, X, ARCH, lens, bias_scale=3.0)
