@@ -10,7 +10,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdit.so")
+# DIT_LIB_PATH: another build of the same library (A/B timing of two builds in one session)
+LIB_PATH = os.environ.get("DIT_LIB_PATH") or os.path.join(_HERE, "libdit.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(f"{LIB_PATH} is not built; run `python -m paper_2510_02838_amd.build` "

@@ -100,6 +100,7 @@ struct dit_ctx {
   int next_slot = 0;
   int pdim = 0;
   float* gemm_partial = nullptr;   // split-K scratch inside the workspace of the running call
+  bool launch_refused = false;     // a product of the running call was outside the GEMM's limits
   // largest |value| of every norm-gain vector (host copy, refreshed lazily after the weights change)
   std::unordered_map<std::string, float> gain_absmax;
   bool gain_stats_valid = false;
@@ -426,7 +427,7 @@ void run_gemm(dit_ctx* c, std::initializer_list<GemmProblem> ps) {
   if (!b.n) return;
   b.partial = c->gemm_partial; b.partial_bytes = c->gemm_partial ? GEMM_PARTIAL_BYTES : 0;
   Scope sc(c, DIT_PROF_GEMM, flop, bytes);
-  launch_gemm(c->stream, b);
+  if (launch_gemm(c->stream, b) < 0) c->launch_refused = true;     // shape outside the kernels' limits: reported by the call
 }
 
 dit_status do_tap(dit_ctx* c, const std::string& name, const void* src, int rows, int cols, int elem, int ld) {
@@ -726,6 +727,7 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
   hipStream_t s = c->stream;
   Run R{c, P, L, c->ws};
   c->gemm_partial = (float*)(c->ws + L.partial);
+  c->launch_refused = false;
   const int Rr = T * n_req;
   {
     // one host image [meta | sigma | a | b], matching the first regions of the workspace; it
@@ -857,6 +859,7 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
     }
   }
   HIPCHK(c, hipGetLastError());
+  if (c->launch_refused) return fail(c, DIT_ESHAPE, "a matrix product of this call exceeds the GEMM kernels' 4 GiB operand limit");
   return DIT_OK;
 }
 
@@ -1105,7 +1108,7 @@ dit_status dit_op_gemm(void* stream, const void* A, int lda, const void* W, int 
   if (M == 0 || N == 0) return DIT_OK;
   GemmBatch b; b.n = 1; b.total_tiles = 0;
   b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc, gate, gate_stride, row_req);
-  launch_gemm((hipStream_t)stream, b, 0);
+  if (launch_gemm((hipStream_t)stream, b, 0) < 0) return DIT_ESHAPE;
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }
 
@@ -1123,7 +1126,7 @@ dit_status dit_op_gemm_qknorm(void* stream, const void* A, int lda, const void* 
   GemmBatch b; b.n = 1; b.total_tiles = 0;
   b.p[0] = with_qknorm(mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, OUT_BF16, out, ldc), nq, nk,
                        head_dim, qgain, kgain, (const float2*)rope, dst_row, (bf16_t*)qo, (bf16_t*)ko, ldo, qscale);
-  launch_gemm((hipStream_t)stream, b, 0);
+  if (launch_gemm((hipStream_t)stream, b, 0) < 0) return DIT_ESHAPE;
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }
 
@@ -1141,7 +1144,7 @@ dit_status dit_op_gemm_splitk(void* stream, const void* A, int lda, const void* 
   GemmBatch b; b.n = 1; b.total_tiles = 0;
   b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc, gate, gate_stride, row_req);
   b.splits = splits; b.partial = (float*)work; b.partial_bytes = work_bytes;
-  launch_gemm((hipStream_t)stream, b, 40128128);
+  if (launch_gemm((hipStream_t)stream, b, 40128128) < 0) return DIT_ESHAPE;
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }
 
@@ -1170,7 +1173,7 @@ dit_status dit_op_gemm_splitk_static(void* stream, const void* A, int lda, const
   // every partial tile the reduction reads is written in full by the product kernel of the
   // same call, so nothing of the previous call's contents has to be cleared
   b.splits = splits; b.partial = (float*)ptr; b.partial_bytes = DIT_STATIC_SCRATCH_BYTES;
-  launch_gemm((hipStream_t)stream, b, 40128128);
+  if (launch_gemm((hipStream_t)stream, b, 40128128) < 0) return DIT_ESHAPE;
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }
 
@@ -1182,7 +1185,7 @@ dit_status dit_op_gemm_variant(void* stream, const void* A, int lda, const void*
   if (lda % 8 || ldw % 8 || ldc % (out_kind == 1 ? 4 : 8) || ((uintptr_t)out & 15)) return DIT_ESHAPE;
   GemmBatch b; b.n = 1; b.total_tiles = 0;
   b.p[0] = mk((const bf16_t*)A, lda, (const bf16_t*)W, ldw, bias, M, N, K, out_kind, out, ldc);
-  launch_gemm((hipStream_t)stream, b, variant);
+  if (launch_gemm((hipStream_t)stream, b, variant) < 0) return DIT_ESHAPE;
   return hipGetLastError() == hipSuccess ? DIT_OK : DIT_EDEVICE;
 }
 
