@@ -59,13 +59,13 @@ struct Plan {
   // device copies (offsets into the workspace meta region)
   size_t o_cu_txt, o_cu_img, o_cu_joint, o_vt_off, o_vtx_off, o_lat_off, o_req_dims, o_tok, o_row_req_s,
       o_row_req_j, o_s2j, o_j2s, o_src_of_col, o_src_of_col_j, o_src_of_col_x, o_tok_of_row, o_tiles, o_xtiles,
-      o_txt_rows;
+      o_txt_rows, o_vtcol_s, o_vtcol_j;
   size_t meta_bytes = 0;
   std::vector<unsigned char> meta;       // host image of the meta region
 };
 
 struct WsLayout {
-  size_t meta, sig, coef_a, coef_b, feat, th1, vec, mhi, mlo, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, vtlo, o, act, cproj,
+  size_t meta, sig, coef_a, coef_b, feat, th1, vec, mhi, mlo, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, vtx, vtlo, o, act, cproj,
       patch, yfin, rope, partial, total;
   int MC = 0;        // modulation columns per conditioning row
   int R = 0;         // conditioning rows = steps * n_req
@@ -285,6 +285,7 @@ void build_plan(const dit_ctx* c, int n_req, const dit_req* reqs, Plan& P) {
   std::vector<int> row_req_s(P.Ns), row_req_j(P.Nj), s2j(P.Ns), j2s(P.Nj), tok_of_row(P.Nj, -1);
   std::vector<int> src_of_col(P.Nv_pad, -1), src_of_col_j(P.Nv_pad, -1), src_of_col_x(P.Nvx_pad, -1);
   std::vector<int> txt_rows(std::max(P.Nt, 1));
+  std::vector<int> vtcol_s(P.Ns), vtcol_j(P.Nj);      // V^T column of every stream row / joint row
   int longest = 0;
   for (int r = 0; r < n_req; ++r) longest = std::max(longest, P.cu_joint[r + 1] - P.cu_joint[r]);
   P.qb = attn_q_per_tile(longest, g.head_dim);
@@ -305,6 +306,8 @@ void build_plan(const dit_ctx* c, int n_req, const dit_req* reqs, Plan& P) {
     for (int t = 0; t < nj; ++t) {
       src_of_col[P.vt_off[r] + t] = j2s[P.cu_joint[r] + t];
       src_of_col_j[P.vt_off[r] + t] = P.cu_joint[r] + t;
+      vtcol_j[P.cu_joint[r] + t] = P.vt_off[r] + t;
+      vtcol_s[j2s[P.cu_joint[r] + t]] = P.vt_off[r] + t;
     }
     for (int t = 0; t < nt; ++t) src_of_col_x[P.vtx_off[r] + t] = P.cu_txt[r] + t;
     for (int q0 = 0; q0 < nj; q0 += P.qb) P.tiles.push_back(AttnTile{r, q0});
@@ -324,6 +327,7 @@ void build_plan(const dit_ctx* c, int n_req, const dit_req* reqs, Plan& P) {
   P.o_src_of_col_x = put(m, src_of_col_x); P.o_tok_of_row = put(m, tok_of_row);
   P.o_tiles = put(m, P.tiles); P.o_xtiles = put(m, P.xtiles);
   P.o_txt_rows = put(m, txt_rows);
+  P.o_vtcol_s = put(m, vtcol_s); P.o_vtcol_j = put(m, vtcol_j);
   P.meta_bytes = rup(m.size(), 256);
   m.resize(P.meta_bytes);
 }
@@ -367,8 +371,9 @@ void layout_ws(const dit_ctx* c, const Plan& P, int max_steps, WsLayout& L) {
   L.qkv = take(std::max(Ns, Nj) * 3 * d * 2);
   L.q = take(Nj * d * 2);
   L.k = take(std::max(Nj, Nt) * d * 2);
-  L.vt = take(d * (size_t)std::max(P.Nv_pad, P.Nvx_pad) * 2);
-  L.vtlo = take(g.family == DIT_FAMILY_W ? d * (size_t)P.Nvx_pad * 2 : 0);   // cross-attention values, second term
+  L.vt = take(d * (size_t)P.Nv_pad * 2);         // self-attention values, transposed (pad columns stay zero for a whole call)
+  L.vtx = take(g.family == DIT_FAMILY_W ? d * (size_t)P.Nvx_pad * 2 : 0);    // cross-attention values: first ...
+  L.vtlo = take(g.family == DIT_FAMILY_W ? d * (size_t)P.Nvx_pad * 2 : 0);   // ... and second term
   L.o = take(Ns * d * 2);
   L.act = take(std::max(std::max(Ns * dff, Nj * wide) * 2, Nt * 2 * d * 4));    // (family W: fp32 keys|values of the condition)
   L.cproj = take(g.family == DIT_FAMILY_W ? Nt * d * 2 * 2 : 0);               // projected condition as two bf16 terms
@@ -412,6 +417,11 @@ GemmProblem with_qknorm(GemmProblem p, int nq, int nk, int head_dim, const float
                         const float2* rope, const int* dst_row, bf16_t* qo, bf16_t* ko, int ldo, float qscale) {
   p.out_kind = OUT_QKNORM;
   p.qk = QkNorm{nq, nk, head_dim, qgain, kgain, rope, dst_row, qo, ko, ldo, qscale};
+  return p;
+}
+// ... and whose value columns go out transposed, row m to column vt_col[m] of vt[H*dh][ldvt]
+GemmProblem with_vt(GemmProblem p, bf16_t* vt, int ldvt, const int* vt_col) {
+  p.qk.vt = vt; p.qk.ldvt = ldvt; p.qk.vt_col = vt_col;
   return p;
 }
 void run_gemm(dit_ctx* c, std::initializer_list<GemmProblem> ps) {
@@ -518,16 +528,16 @@ dit_status joint_block(dit_ctx* c, const Run& R, const std::string& p, const flo
   GemmProblem pq_t = mk(h, d, Wm(c, pt + ".qkv.w"), Wld(c, pt + ".qkv.w"), Wv(c, pt + ".qkv.b"), Nt, 3 * d, d, OUT_BF16, qkv, 3 * d);
   GemmProblem pq_i = mk(h + (size_t)Nt * d, d, Wm(c, pi + ".qkv.w"), Wld(c, pi + ".qkv.w"), Wv(c, pi + ".qkv.b"), Ni, 3 * d, d, OUT_BF16, qkv + (size_t)Nt * 3 * d, 3 * d);
   if (fuse) {
-    pq_t = with_qknorm(pq_t, d, d, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, qs);
-    pq_i = with_qknorm(pq_i, d, d, g.head_dim, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"), rope, s2j + Nt, q, k, d, qs);
+    const int* vtc = R.ip(P.o_vtcol_s);
+    pq_t = with_vt(with_qknorm(pq_t, d, d, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, qs), vt, P.Nv_pad, vtc);
+    pq_i = with_vt(with_qknorm(pq_i, d, d, g.head_dim, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"), rope, s2j + Nt, q, k, d, qs), vt, P.Nv_pad, vtc + Nt);
   }
   run_gemm(c, {pq_t, pq_i});
   TAP(pt + ".qkv", qkv, Nt, 3 * d, 2, 3 * d); TAP(pi + ".qkv", qkv + (size_t)Nt * 3 * d, Ni, 3 * d, 2, 3 * d);
-  {
-    Scope sc(c, DIT_PROF_QKNORM, 0, (fuse ? 4.0 : 12.0) * Ns * d);
-    if (!fuse)
-      launch_qknorm_rope(c->stream, qkv, 3 * d, Ns, g.n_heads, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, d, 1,
-                         Nt, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"), qs);
+  if (!fuse) {
+    Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Ns * d);
+    launch_qknorm_rope(c->stream, qkv, 3 * d, Ns, g.n_heads, g.head_dim, Wv(c, pt + ".qnorm.g"), Wv(c, pt + ".knorm.g"), rope, s2j, q, k, d, d, 1,
+                       Nt, Wv(c, pi + ".qnorm.g"), Wv(c, pi + ".knorm.g"), qs);
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col), P.Nv_pad, vt, P.Nv_pad);
   }
   TAP(p + ".q", q, P.Nj, d, 2, d); TAP(p + ".k", k, P.Nj, d, 2, d);
@@ -571,14 +581,13 @@ dit_status single_block(dit_ctx* c, const Run& R, const std::string& p, const fl
   const bool fuse = c->taps.empty();          // see joint_block
   const float qs = attn_qscale(g.head_dim);
   GemmProblem pq = mk(h, d, w1, ld1, b1, Nj, 3 * d, d, OUT_BF16, qkv, 3 * d);
-  if (fuse) pq = with_qknorm(pq, d, d, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, qs);
+  if (fuse) pq = with_vt(with_qknorm(pq, d, d, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, qs), vt, P.Nv_pad, R.ip(P.o_vtcol_j));
   run_gemm(c, {pq, mk(h, d, w1 + (size_t)3 * d * ld1, ld1, b1 + 3 * d, Nj, dff, d, OUT_GELU_BF16, cat + d, wide)});
   TAP(p + ".lin1", qkv, Nj, 3 * d, 2, 3 * d);
-  {
-    Scope sc(c, DIT_PROF_QKNORM, 0, (fuse ? 4.0 : 12.0) * Nj * d);
-    if (!fuse)
-      launch_qknorm_rope(c->stream, qkv, 3 * d, Nj, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
-                         -1, nullptr, nullptr, qs);
+  if (!fuse) {
+    Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Nj * d);
+    launch_qknorm_rope(c->stream, qkv, 3 * d, Nj, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
+                       -1, nullptr, nullptr, qs);
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col_j), P.Nv_pad, vt, P.Nv_pad);
   }
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, cat, wide, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
@@ -613,13 +622,12 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
   const bool fuse = c->taps.empty();          // see joint_block
   const float qs = attn_qscale(g.head_dim);
   GemmProblem pq = mk(h, d, Wm(c, p + ".qkv.w"), Wld(c, p + ".qkv.w"), Wv(c, p + ".qkv.b"), Ni, 3 * d, d, OUT_BF16, qkv, 3 * d);
-  if (fuse) pq = with_qknorm(pq, d, d, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, qs);
+  if (fuse) pq = with_vt(with_qknorm(pq, d, d, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, qs), vt, P.Nv_pad, R.ip(P.o_vtcol_s));
   run_gemm(c, {pq});
-  {
-    Scope sc(c, DIT_PROF_QKNORM, 0, (fuse ? 4.0 : 12.0) * Ni * d);
-    if (!fuse)
-      launch_qknorm_rope(c->stream, qkv, 3 * d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
-                         -1, nullptr, nullptr, qs);
+  if (!fuse) {
+    Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Ni * d);
+    launch_qknorm_rope(c->stream, qkv, 3 * d, Ni, g.n_heads, g.head_dim, Wv(c, p + ".qnorm.g"), Wv(c, p + ".knorm.g"), rope, nullptr, q, k, d, d, 1,
+                       -1, nullptr, nullptr, qs);
     launch_v_transpose(c->stream, qkv, 3 * d, 2 * d, g.n_heads, g.head_dim, R.ip(P.o_src_of_col), P.Nv_pad, vt, P.Nv_pad);
   }
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, o, d, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
@@ -645,15 +653,16 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
   pxq.qk.f16 = 1;
   float* kv32 = R.at<float>(L.act);
   bf16_t* cproj_lo = cproj + (size_t)Nt * d;
+  bf16_t* vtx = R.at<bf16_t>(L.vtx);
   bf16_t* vtlo = R.at<bf16_t>(L.vtlo);
   run_gemm(c, {pxq, mk(cproj, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), Wv(c, p + ".xkv.b"), Nt, 2 * d, d, OUT_F32, kv32, 2 * d)});
   run_gemm(c, {mk(cproj_lo, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), nullptr, Nt, 2 * d, d, OUT_RESID_F32, kv32, 2 * d)});
   {
     Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Nt * d);
     launch_cross_kv_finish(c->stream, kv32, 2 * d, Nt, g.n_heads, g.head_dim, Wv(c, p + ".xknorm.g"), k, d,
-                           R.ip(P.o_src_of_col_x), P.Nvx_pad, vt, vtlo, P.Nvx_pad);
+                           R.ip(P.o_src_of_col_x), P.Nvx_pad, vtx, vtlo, P.Nvx_pad);
   }
-  run_attention(c, R, q, d, k, d, vt, P.Nvx_pad, o, d, R.ip(P.o_cu_img), R.ip(P.o_cu_txt), R.ip(P.o_vtx_off),
+  run_attention(c, R, q, d, k, d, vtx, P.Nvx_pad, o, d, R.ip(P.o_cu_img), R.ip(P.o_cu_txt), R.ip(P.o_vtx_off),
                 (const AttnTile*)(R.ws + L.meta + P.o_xtiles), (int)P.xtiles.size(), nullptr, P.xattn_flop,
                 gmax(c, p + ".xqnorm.g"), gmax(c, p + ".xknorm.g"), vtlo);
   TAP(p + ".xattn", o, Ni, d, 2, d);
@@ -784,6 +793,9 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
       for (int l = 0; l < g.n_single; ++l) { snprintf(nb, sizeof nb, "sgl%d.mod", l); modv(nb, 3 * d); }
     }
     modv("final.mod", 2 * d);
+    // the QKV epilogue writes only the columns of real tokens: the pad columns of every request's
+    // transposed values (up to the next multiple of 64) are zeroed here, once for all steps and blocks
+    launch_fill_u16(s, R.at<bf16_t>(L.vt), (long long)d * P.Nv_pad, 0);
     if (has_rope)
       launch_rope_table(s, tok, R.ip(P.o_tok_of_row), P.Nj, g.head_dim, g.rope_axes[0], g.rope_axes[1], g.rope_axes[2], g.rope_theta, R.at<float2>(L.rope));
   }

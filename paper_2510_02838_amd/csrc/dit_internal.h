@@ -21,7 +21,8 @@ inline bool first_use_on_device(std::atomic<unsigned>& mask) {
 // ---- GEMM ---------------------------------------------------------------------------
 enum { OUT_BF16 = 0, OUT_F32 = 1, OUT_GELU_BF16 = 2, OUT_RESID_F32 = 3, OUT_QKNORM = 4 };
 
-// OUT_QKNORM: output columns [0, nq) are queries and [nq, nq+nk) keys: per head RMS norm (eps
+// OUT_QKNORM (only in the tile variants whose waves own 64 output columns): output columns [0, nq) are
+// queries and [nq, nq+nk) keys: per head RMS norm (eps
 // 1e-6) times gain, rotary code, queries times qscale, written as bf16 to qo / ko at row
 // dst_row[m] (or m), column = column inside the q (k) range.  Columns from nq+nk on are written
 // as OUT_BF16 to `out`.  nq and nk are multiples of 256, head_dim is 64 or 128.
@@ -33,6 +34,10 @@ struct QkNorm {
   bf16_t* qo; bf16_t* ko; int ldo;
   float qscale;
   int f16 = 0;                              // store q / k as fp16 instead of bf16
+  // optional: the value columns (from nq+nk on) go out TRANSPOSED instead of to `out`:
+  // vt[(n - nq - nk) * ldvt + vt_col[m]] = bf16(acc + bias); columns of vt that no row maps to are left alone
+  bf16_t* vt = nullptr; int ldvt = 0;
+  const int* vt_col = nullptr;              // [M]
 };
 
 struct GemmProblem {

@@ -562,8 +562,72 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
       }
     }
   };
+  // value columns of a QKV product written transposed (the layout the attention kernel reads): the
+  // wave's 32-row patch goes through LDS column-major, and a lane writes two consecutive rows of one
+  // output column as one 4-byte piece when they are neighbours in the transposed matrix (always, except
+  // across a request boundary or at an odd start), else as single elements.
+  auto epilogue_vt = [&]() {
+   if constexpr (BN / WN == 64) {                      // (the tile variants that take q/k-norm problems)
+    const QkNorm& Q = P.qk;
+    constexpr int CS = 36 * 4;                         // bytes per patch column: 32 rows + padding, 16-byte aligned
+    static_assert(TN * 32 * CS <= 32 * RS, "transposed patch fits the wave's staging area");
+    const int nv0 = n0 + wn * (BN / WN) - (Q.nq + Q.nk);   // first value column of the wave
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          *(float*)(stg + (j * 32 + (lane & 31)) * CS + (8 * (e >> 2) + 4 * half + (e & 3)) * 4) = acc[i][j][e];
+      asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+      const int mb = m0 + wm * (BM / WM) + i * 32;     // first row of the patch
+      // whole patch in range, its 32 rows neighbours in the transposed matrix, starting at a multiple of 8:
+      // a lane writes 8 rows of one column as one 16-byte piece
+      bool fast = mb + 32 <= P.M;
+      int cb = 0;
+      if (fast) {
+        cb = Q.vt_col[mb];
+        fast = (cb & 7) == 0 && Q.vt_col[mb + 31] == cb + 31;
+      }
+      if (fast) {
+        const int rg = lane & 3, cl = lane >> 2;
+#pragma unroll
+        for (int it = 0; it < TN * 32 / 16; ++it) {
+          const int col = it * 16 + cl, nv = nv0 + col;
+          const f32x4 t0 = *(const f32x4*)(stg + col * CS + rg * 32), t1 = *(const f32x4*)(stg + col * CS + rg * 32 + 16);
+          if (nv + Q.nq + Q.nk >= P.N) continue;
+          const float bv = P.bias ? P.bias[nv + Q.nq + Q.nk] : 0.f;
+          u32x4 w = {pack2bf(t0[0] + bv, t0[1] + bv), pack2bf(t0[2] + bv, t0[3] + bv), pack2bf(t1[0] + bv, t1[1] + bv), pack2bf(t1[2] + bv, t1[3] + bv)};
+          *(u32x4*)(Q.vt + (size_t)nv * Q.ldvt + cb + rg * 8) = w;
+        }
+      } else {
+        const int rp = lane & 15, cl = lane >> 4;      // this lane's row pair and column phase
+        const int m = mb + 2 * rp;
+        const bool ok0 = m < P.M, ok1 = m + 1 < P.M;
+        const int c0 = ok0 ? Q.vt_col[m] : 0, c1 = ok1 ? Q.vt_col[m + 1] : -1;
+        const bool pair = ok1 && c1 == c0 + 1 && (c0 & 1) == 0;
+#pragma unroll
+        for (int it = 0; it < TN * 32 / 4; ++it) {
+          const int col = it * 4 + cl;                 // column inside the wave's patch
+          const int nv = nv0 + col;                    // value column = row of the transposed matrix
+          const f32x2 t2 = *(const f32x2*)(stg + col * CS + rp * 8);
+          if (nv + Q.nq + Q.nk >= P.N) continue;
+          const float bv = P.bias ? P.bias[nv + Q.nq + Q.nk] : 0.f;
+          bf16_t* dst = Q.vt + (size_t)nv * Q.ldvt;
+          if (pair) *(uint32_t*)(dst + c0) = pack2bf(t2[0] + bv, t2[1] + bv);
+          else {
+            if (ok0) dst[c0] = f2bf(t2[0] + bv);
+            if (ok1) dst[c1] = f2bf(t2[1] + bv);
+          }
+        }
+      }
+      asm volatile("" ::: "memory");
+    }
+   }
+  };
   if (P.out_kind == OUT_QKNORM) {
     if (n0 < P.qk.nq + P.qk.nk) epilogue_qk();
+    else if (P.qk.vt) epilogue_vt();
     else epilogue(std::integral_constant<int, OUT_BF16>{});
   }
   else if (P.out_kind == OUT_BF16) epilogue(std::integral_constant<int, OUT_BF16>{});
