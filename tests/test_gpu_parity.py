@@ -67,10 +67,10 @@ def test_set_get_tensor_round_trip(torch, B):
 
 # ---------------------------------------------------------------------------------- GEMM
 @pytest.mark.parametrize("M,N,K", [(300, 384, 256), (1, 256, 64), (517, 1000, 192), (4250, 1536, 1536)])
-@pytest.mark.parametrize("variant", [0, 128128, 10128128, 30128128, 256256, 1256256, 10256256, 11256256, 20256256, 21256256,
+@pytest.mark.parametrize("variant", [0, 128128, 10128128, 30128128, 256256, 1256256, 1320256, 10256256, 11256256, 20256256, 21256256,
                                      256128, 128256, 31256128, 32256128, 31128256])
 def test_gemm_against_float64_matmul(torch, B, M, N, K, variant):
-    if M > 1000 and variant not in (0, 1256256, 11256256, 128128, 32256128):
+    if M > 1000 and variant not in (0, 1256256, 1320256, 11256256, 128128, 32256128):
         pytest.skip("large shape only for the production tiles")
     A = rnd(1, "A", (M, K))
     W = rnd(2, "W", (N, K), 0.05)
@@ -193,7 +193,8 @@ def test_gemm_split_k(torch, B, M, N, K, splits):
 
 
 @pytest.mark.parametrize("M,d,dh,parts", [(300, 256, 64, "qkv"), (517, 512, 128, "qkv"), (70, 256, 128, "q"),
-                                          (4250, 512, 64, "qkv"), (33, 256, 64, "kv")])
+                                          (4250, 512, 64, "qkv"), (33, 256, 64, "kv"),
+                                          (4250, 1536, 64, "qkv"), (5400, 1024, 128, "qkv")])
 def test_gemm_qknorm_epilogue(torch, B, M, d, dh, parts):
     """QKV product with the q/k RMS norm, rotary code, scale and row scatter as its epilogue,
     against the float64 product pushed through the oracle's norm and rotation."""
