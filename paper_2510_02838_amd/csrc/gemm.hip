@@ -392,6 +392,22 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 #pragma unroll
       for (int c = 0; c < VEC; ++c) { cs[c] = 0.f; cq[c] = 0.f; }
     }
+    // Gated residual: the loads of an output row (request index -> gate vector, and the residual itself)
+    // depend on each other and may not be moved across the stores by the compiler, so they are issued
+    // by hand for all rows of a 32-row patch at once: two memory latencies per patch instead of two per row.
+    constexpr int NIT = 32 / RPI;
+    constexpr bool RESID = KIND == OUT_RESID_F32;
+    int rq[RESID ? NIT : 1];
+    auto load_rq = [&](int i) {
+      if constexpr (RESID) {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+          const int m = m0 + wm * (BM / WM) + i * 32 + it * RPI + lr;
+          rq[it] = (P.row_req && m < P.M) ? P.row_req[m] : 0;
+        }
+      }
+    };
+    load_rq(0);
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -399,9 +415,29 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 #pragma unroll
         for (int e = 0; e < 16; ++e)
           *(float*)(stg + (8 * (e >> 2) + 4 * half + (e & 3)) * RS + (j * 32 + (lane & 31)) * 4) = acc[i][j][e];
+      f32x4 xr[RESID ? NIT : 1], gr[RESID ? NIT : 1];
+      // (tiles with 128 or more accumulator registers per lane fetch half a patch at a time)
+      constexpr int GRP = (RESID && TM * TN >= 8) ? NIT / 2 : NIT;
+      auto load_resid = [&](int first) {
+        if constexpr (RESID) {
+#pragma unroll
+          for (int it = first; it < first + GRP; ++it) {
+            const int m = m0 + wm * (BM / WM) + i * 32 + it * RPI + lr;
+            xr[it] = f32x4{0.f, 0.f, 0.f, 0.f};
+            gr[it] = f32x4{1.f, 1.f, 1.f, 1.f};
+            if (full && m < P.M) {
+              xr[it] = *(const f32x4*)((const float*)P.out + (size_t)m * P.ldc + n);
+              if (P.gate) gr[it] = *(const f32x4*)(P.gate + (size_t)rq[it] * P.gate_stride + n);
+            }
+          }
+        }
+      };
+      load_resid(0);
       asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-      for (int it = 0; it < 32 / RPI; ++it) {
+      for (int it = 0; it < NIT; ++it) {
+        if (GRP < NIT && it == GRP) load_resid(GRP);
+        if (RESID && it == NIT - 1 && i + 1 < TM) load_rq(i + 1);
         const int row = it * RPI + lr;
         const int m = m0 + wm * (BM / WM) + i * 32 + row;
         float v[VEC];
@@ -414,20 +450,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
         if (m >= P.M || n >= P.N) continue;
         const size_t o = (size_t)m * P.ldc + n;
         if constexpr (KIND == OUT_RESID_F32) {
-          const float* gp = P.gate ? P.gate + (size_t)(P.row_req ? P.row_req[m] : 0) * P.gate_stride + n : nullptr;
           float* xp = (float*)P.out + o;
           if (full) {
-            f32x4 x4 = *(const f32x4*)xp;
-            f32x4 g4 = {1.f, 1.f, 1.f, 1.f};
-            if (gp) g4 = *(const f32x4*)gp;
+            f32x4 x4 = xr[it];
 #pragma unroll
-            for (int c = 0; c < 4; ++c) x4[c] += g4[c] * v[c];
+            for (int c = 0; c < 4; ++c) x4[c] += gr[it][c] * v[c];
             *(f32x4*)xp = x4;
             if constexpr (STATS) {
 #pragma unroll
               for (int c = 0; c < 4; ++c) { cs[c] += x4[c]; cq[c] += x4[c] * x4[c]; }
             }
           } else {
+            const float* gp = P.gate ? P.gate + (size_t)rq[it] * P.gate_stride + n : nullptr;
             for (int c = 0; c < VEC && n + c < P.N; ++c) {
               const float r = xp[c] + (gp ? gp[c] : 1.f) * v[c];
               xp[c] = r;
@@ -504,6 +538,18 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
       float* xch = (float*)(smem + WM * WN * 32 * RS);   // [2][waves][32] partial sums of squares
       static_assert(WM * WN * 32 * RS + 2 * WM * WN * 32 * 4 <= NS * STAGE, "exchange area fits the ring");
       bf16_t* dst = is_k ? Q.ko : Q.qo;
+      // Destination rows one patch ahead, and per patch the rotary pairs of its rows while the patch
+      // turns through LDS: the compiler may not move these loads across the stores, and issued row by row
+      // each would cost a full memory latency.
+      int dnext[4];
+      auto load_drows = [&](int i) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+          const int m = m0 + wm * (BM / WM) + i * 32 + it * RPI + lr;
+          dnext[it] = (Q.dst_row && m < P.M) ? Q.dst_row[m] : m;
+        }
+      };
+      load_drows(0);
 #pragma unroll
       for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -511,6 +557,25 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 #pragma unroll
           for (int e = 0; e < 16; ++e)
             *(float*)(stg + (8 * (e >> 2) + 4 * half + (e & 3)) * RS + (j * 32 + (lane & 31)) * 4) = acc[i][j][e];
+        int drows[4];
+        f32x4 rc0[4], rc1[4];
+        constexpr int RG = TM * TN >= 10 ? 1 : 4;     // (the 320-row tile has no registers to spare: row by row there;
+                                                      //  2 or 4 rows at a time spill and measured slower)
+        auto load_rope = [&](int first) {
+#pragma unroll
+          for (int it = first; it < first + RG; ++it) {
+            const int m = m0 + wm * (BM / WM) + i * 32 + it * RPI + lr;
+            rc0[it] = f32x4{1.f, 0.f, 1.f, 0.f}; rc1[it] = f32x4{1.f, 0.f, 1.f, 0.f};      // (cos, sin) pairs
+            if (Q.rope && m < P.M) {
+              const f32x4* rp = (const f32x4*)(Q.rope + (size_t)drows[it] * (Q.head_dim / 2) + (hc >> 1));
+              rc0[it] = rp[0]; rc1[it] = rp[1];
+            }
+          }
+        };
+#pragma unroll
+        for (int it = 0; it < 4; ++it) drows[it] = dnext[it];
+        load_rope(0);
+        if (i + 1 < TM) load_drows(i + 1);
         asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         float v[4][VEC], ss[4];
 #pragma unroll
@@ -539,15 +604,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
         }
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
+          if (RG < 4 && it > 0 && it % RG == 0) load_rope(it);
           const int m = m0 + wm * (BM / WM) + i * 32 + it * RPI + lr;
           if (m >= P.M) continue;
           const float r = rsqrtf(ss[it] * inv_dh + 1e-6f) * osc;
-          const int drow = Q.dst_row ? Q.dst_row[m] : m;
-          f32x4 c0 = {1.f, 0.f, 1.f, 0.f}, c1 = {1.f, 0.f, 1.f, 0.f};      // (cos, sin) pairs
-          if (Q.rope) {
-            const f32x4* rp = (const f32x4*)(Q.rope + (size_t)drow * (Q.head_dim / 2) + (hc >> 1));
-            c0 = rp[0]; c1 = rp[1];
-          }
+          const int drow = drows[it];
+          const f32x4 c0 = rc0[it], c1 = rc1[it];
           const float cs[8] = {c0[0], c0[1], c0[2], c0[3], c1[0], c1[1], c1[2], c1[3]};
           u32x4 w;
 #pragma unroll
@@ -559,6 +621,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
           *(u32x4*)(dst + (size_t)drow * Q.ldo + col_in) = w;
         }
         asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);    // patches one after the other: work hoisted across them costs registers
       }
     }
   };
