@@ -646,13 +646,44 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
       const int mb = m0 + wm * (BM / WM) + i * 32;     // first row of the patch
       // whole patch in range, its 32 rows neighbours in the transposed matrix, starting at a multiple of 8:
       // a lane writes 8 rows of one column as one 16-byte piece
-      bool fast = mb + 32 <= P.M;
+      bool consec = mb + 32 <= P.M;
       int cb = 0;
-      if (fast) {
+      if (consec) {
         cb = Q.vt_col[mb];
-        fast = (cb & 7) == 0 && Q.vt_col[mb + 31] == cb + 31;
+        consec = Q.vt_col[mb + 31] == cb + 31;
       }
-      if (fast) {
+      if (consec && (cb & 7) != 0) {
+        // Neighbours, but starting off a multiple of 8 (a request's image rows follow 154 text rows): three
+        // 16-byte pieces from the first aligned column on, written by lanes 0-2 of each group of four; the
+        // fourth lane writes the 8 rows before and after them as pairs (even start) or single elements.
+        const int r0 = 8 - (cb & 7);                   // patch row of the first aligned column
+        const int rg = lane & 3, cl = lane >> 2;
+#pragma unroll
+        for (int it = 0; it < TN * 32 / 16; ++it) {
+          const int col = it * 16 + cl, nv = nv0 + col;
+          if (nv + Q.nq + Q.nk >= P.N) continue;
+          const float* pc = (const float*)(stg + col * CS);
+          const float bv = P.bias ? P.bias[nv + Q.nq + Q.nk] : 0.f;
+          bf16_t* dst = Q.vt + (size_t)nv * Q.ldvt + cb;
+          if (rg < 3) {
+            const float* t = pc + r0 + 8 * rg;
+            u32x4 w = {pack2bf(t[0] + bv, t[1] + bv), pack2bf(t[2] + bv, t[3] + bv), pack2bf(t[4] + bv, t[5] + bv), pack2bf(t[6] + bv, t[7] + bv)};
+            *(u32x4*)(dst + r0 + 8 * rg) = w;
+          } else if ((cb & 1) == 0) {
+#pragma unroll
+            for (int k = 0; k < 8; k += 2) {
+              const int r = k < r0 ? k : k + 24;
+              *(uint32_t*)(dst + r) = pack2bf(pc[r] + bv, pc[r + 1] + bv);
+            }
+          } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) {
+              const int r = k < r0 ? k : k + 24;
+              dst[r] = f2bf(pc[r] + bv);
+            }
+          }
+        }
+      } else if (consec) {
         const int rg = lane & 3, cl = lane >> 2;
 #pragma unroll
         for (int it = 0; it < TN * 32 / 16; ++it) {
