@@ -99,6 +99,16 @@ const char* dit_last_error(const dit_ctx* ctx);
 size_t dit_weight_bytes(const dit_ctx* ctx);
 size_t dit_workspace_bytes(const dit_ctx* ctx, int n_req, const dit_req* reqs, int max_steps);
 
+/* How the self-attention launch of a request list is cut up (host arithmetic only, no device call):
+ * out[0] queries per workgroup (128 or 256), out[1] query blocks per head, out[2] how many of these
+ * blocks run as key-split shares and out[3] the number of shares each (1: none).  Blocks are split
+ * when all requests have one shape, the head count is a multiple of 8 and the last round of
+ * workgroups would fill less than three quarters of the chip (Appendix "Impact of Batch Size" times
+ * exactly such same-shape batches); the shares' partial sums live in the workspace, are added in a
+ * fixed order, and only the form of attention without a running maximum (bounded q/k-norm gains)
+ * uses them.  DIT_ATTN_SPLIT=0 in the environment switches the splitting off. */
+dit_status dit_attention_plan(const dit_ctx* ctx, int n_req, const dit_req* reqs, int out[4]);
+
 /* Hands the caller's device buffers to the context (both 256-byte aligned).  The
  * workspace may be re-bound at any time; its contents carry nothing between calls.  The
  * library keeps a host copy of the largest |gain| of every q/k norm (it bounds the attention

@@ -45,6 +45,7 @@ _SIGS = {
     "dit_last_error": (C.c_char_p, [_vp]),
     "dit_weight_bytes": (_sz, [_vp]),
     "dit_workspace_bytes": (_sz, [_vp, _i, C.POINTER(dit_req), _i]),
+    "dit_attention_plan": (_i, [_vp, _i, C.POINTER(dit_req), C.POINTER(C.c_int)]),
     "dit_bind": (_i, [_vp, _vp, _sz, _vp, _sz]),
     "dit_init_weights": (_i, [_vp, C.c_uint64, C.c_float]),
     "dit_tensor_count": (_i, [_vp]),
@@ -148,6 +149,12 @@ class DiT:
 
     def workspace_bytes(self, reqs, max_steps):
         return dit_workspace_bytes(self.ctx, len(reqs), make_reqs(reqs), max_steps)
+
+    def attention_plan(self, reqs):
+        """(queries per workgroup, query blocks per head, blocks run as key-split shares, shares each)."""
+        out = (C.c_int * 4)()
+        self.check(dit_attention_plan(self.ctx, len(reqs), make_reqs(reqs), out))
+        return tuple(out)
 
     def ensure_workspace(self, reqs, max_steps):
         need = self.workspace_bytes(reqs, max_steps)

@@ -103,8 +103,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
     int nb = gridDim.x, x = bid & 7, idx = bid >> 3, q = nb >> 3, rem = nb & 7;
     bid = x * q + (x < rem ? x : rem) + idx;
   }
-  const int head = bid / a.n_tiles;
-  const AttnTile tile = a.tiles[bid - head * a.n_tiles];
+  int head = bid / a.n_tiles, tidx = bid - head * a.n_tiles;
+  if (a.hpx > 0) {                // tile-major inside the head group of this XCD
+    const int per = a.n_tiles * a.hpx, grp = bid / per, idx = bid - grp * per;
+    tidx = idx / a.hpx;
+    head = grp * a.hpx + (idx - tidx * a.hpx);
+  }
+  const AttnTile tile = a.tiles[tidx];
   const int seg = tile.seg;
   const int qbeg = a.cu_q[seg], qlen = a.cu_q[seg + 1] - qbeg;
   const int kbeg = a.cu_k[seg], klen = a.cu_k[seg + 1] - kbeg;
@@ -136,7 +141,9 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
     int q = i * NT + tid, r = q >> 3, pc = q & 7, c = pc ^ ((r >> 1) & 7);
     gv[i] = (uint32_t)(head * DH + r) * (uint32_t)a.ldvt + vcol0 + c * 8;
   }
-  const int n_kt = (klen + KT - 1) / KT;
+  const int n_kt_all = (klen + KT - 1) / KT;
+  const int kt_first = tile.parts > 0 ? tile.kt0 : 0;                       // this workgroup's share of the key tiles
+  const int n_kt = tile.parts > 0 ? tile.kt0 + tile.nkt : n_kt_all;         // (one past its last tile)
   auto issue_k = [&](int kt) {
     unsigned char* dst = sKb + (kt & 1) * KBYTES;
 #pragma unroll
@@ -225,13 +232,13 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
   const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 
   // ---- prologue: scores of tile 0 --------------------------------------------------------
-  issue_k(0);
+  issue_k(kt_first);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
-  if (n_kt > 1) issue_k(1);
-  issue_v(0);
+  if (kt_first + 1 < n_kt) issue_k(kt_first + 1);
+  issue_v(kt_first);
   f32x16 sc[2], sn[2];     // score tiles of the current and the next key tile
-  scores(0, sc);
+  scores(kt_first, sc);
   float mx = row_max(sc);
 
   // One iteration; `sc` holds S(kt) on entry, `sn` receives S(kt+1).  The loop below calls it
@@ -300,7 +307,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
     // loads): they cannot raise the max, and their V^T columns are zero, so O is unaffected;
     // only their share of the row sum has to be taken out again.
     // Register e of tile t holds key  kt*64 + 32t + 16*(e/8) + 8*half + e%8.
-    if (kt == n_kt - 1 && (klen & (KT - 1)) != 0) {
+    if (kt == n_kt_all - 1 && (klen & (KT - 1)) != 0) {
       float corr = 0.f;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
@@ -314,13 +321,82 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
       l_run -= corr;
     }
   };
-  for (int kt = 0; kt < n_kt; kt += 2) {
+  for (int kt = kt_first; kt < n_kt; kt += 2) {
     step(kt, sc, sn);
     if (kt + 1 < n_kt) step(kt + 1, sn, sc);
   }
 
+  float l_tot = xhalf_sum(l_run);
+  // ---- key-split block: leave the unnormalised sums; the last share to arrive adds them up ----
+  if constexpr (MODE == 2) {
+    if (tile.parts > 0) {
+      constexpr int PSZ = NW * 32 * (DH + 1);          // floats per share: O^T in register order, then the row sums
+      float* const base = a.part + ((size_t)(head * a.n_slots + tile.slot) * tile.parts) * PSZ;
+      float* const mine = base + (size_t)tile.part * PSZ;
+      // Device-scope stores and, on the other side, device-scope loads: they go through to the level all XCDs
+      // share, so no cache has to be written back or invalidated as a whole (a release fence walks this XCD's
+      // L2 once per share and a full fence also drops every K and V^T line it holds for the workgroups still
+      // running: measured 1.5 and 1.8 times the time of the launch without shares).
+      typedef float f32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+      for (int d = 0; d < ND; ++d)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 v4 = {o[d][4 * g], o[d][4 * g + 1], o[d][4 * g + 2], o[d][4 * g + 3]};
+          float* p4 = mine + (((wave * ND + d) * 4 + g) * 64 + lane) * 4;
+          asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" :: "v"(p4), "v"(v4) : "memory");
+        }
+      if (half == 0)
+        __hip_atomic_store((unsigned*)(mine + NW * 32 * DH + wave * 32 + l32), __float_as_uint(l_tot), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // my sums have arrived before my count
+      __syncthreads();                                 // (also: every wave is done with the LDS tiles)
+      if (tid == 0) {
+        const unsigned old = atomicAdd(a.part_cnt + head * a.n_slots + tile.slot, 1u);
+        const int last = old == (unsigned)(tile.parts - 1);
+        if (last) atomicExch(a.part_cnt + head * a.n_slots + tile.slot, 0u);   // ready for the next launch
+        *(volatile int*)smem = last;
+      }
+      __syncthreads();
+      if (*(volatile int*)smem == 0) return;
+      // Fixed order of summation (share 0, 1, ...; my own from registers, the same values I stored): the result
+      // does not depend on which share finished last.
+      f32x16 mo[ND];
+#pragma unroll
+      for (int d = 0; d < ND; ++d) mo[d] = o[d];
+      const float ml = l_tot;
+      l_tot = 0.f;
+#pragma unroll
+      for (int d = 0; d < ND; ++d)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) o[d][e] = 0.f;
+      for (int pt = 0; pt < tile.parts; ++pt) {
+        if (pt == tile.part) {
+#pragma unroll
+          for (int d = 0; d < ND; ++d)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) o[d][e] += mo[d][e];
+          l_tot += ml;
+          continue;
+        }
+        const float* src = base + (size_t)pt * PSZ;
+#pragma unroll
+        for (int d = 0; d < ND; ++d)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const float* p4 = src + (((wave * ND + d) * 4 + g) * 64 + lane) * 4;
+#pragma unroll
+            for (int c = 0; c < 4; c += 2) {
+              const unsigned long long u = __hip_atomic_load((const unsigned long long*)(p4 + c), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+              o[d][4 * g + c] += __uint_as_float((unsigned)u);
+              o[d][4 * g + c + 1] += __uint_as_float((unsigned)(u >> 32));
+            }
+          }
+        l_tot += __uint_as_float(__hip_atomic_load((const unsigned*)(src + NW * 32 * DH + wave * 32 + l32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      }
+    }
+  }
+
   // ---- normalise and store -------------------------------------------------------------------
-  const float l_tot = xhalf_sum(l_run);
   if (q_ok) {
     const float inv = 1.0f / l_tot;
     const int qrow = qbeg + qi;

@@ -55,18 +55,20 @@ struct Plan {
   std::vector<int> cu_txt, cu_img, cu_joint, vt_off, vtx_off;
   std::vector<long long> lat_off;
   std::vector<AttnTile> tiles, xtiles;
+  std::vector<AttnTile> tiles_split;    // `tiles` with the blocks of the last, partly filled round split along the keys (or empty)
+  int split_slots = 0, split_parts = 1;
   double attn_flop = 0, xattn_flop = 0;  // per head-dim unit: 4 * sum(nq*nk) * d
   // device copies (offsets into the workspace meta region)
   size_t o_cu_txt, o_cu_img, o_cu_joint, o_vt_off, o_vtx_off, o_lat_off, o_req_dims, o_tok, o_row_req_s,
       o_row_req_j, o_s2j, o_j2s, o_src_of_col, o_src_of_col_j, o_src_of_col_x, o_tok_of_row, o_tiles, o_xtiles,
-      o_txt_rows, o_vtcol_s, o_vtcol_j;
+      o_txt_rows, o_vtcol_s, o_vtcol_j, o_tiles_split, o_split_cnt;
   size_t meta_bytes = 0;
   std::vector<unsigned char> meta;       // host image of the meta region
 };
 
 struct WsLayout {
   size_t meta, sig, coef_a, coef_b, feat, th1, vec, mhi, mlo, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, vtx, vtlo, o, act, cproj,
-      patch, yfin, rope, partial, total;
+      patch, yfin, rope, partial, attn_part, total;
   int MC = 0;        // modulation columns per conditioning row
   int R = 0;         // conditioning rows = steps * n_req
   int ldp = 0, ldy = 0;
@@ -248,6 +250,47 @@ size_t put(std::vector<unsigned char>& m, const std::vector<T>& v) {
   return off;
 }
 
+// Key-split of the attention blocks in the last, partly filled round.  The chip's 8 XCDs take the workgroups
+// of a launch in turn, each running its share in rounds of (32 CUs x workgroups per CU); when every block
+// costs the same (requests of one shape) a launch of 1.6 rounds takes as long as one of 2.  The blocks of the
+// partial round are cut into 2-4 shares of their key tiles, so that this round is made of shorter workgroups
+// that fill all CUs: 102 blocks per XCD on 64 slots become 63 whole blocks and 39 x 3 shares, 1 + 2/3 rounds.
+// Needs a head count that is a multiple of 8 (each XCD owns whole heads: all shares of a block meet in one L2).
+void plan_attention_split(Plan& P, const dit_config& g) {
+  P.tiles_split.clear(); P.split_slots = 0; P.split_parts = 1;
+  static const bool off = [] { const char* e = getenv("DIT_ATTN_SPLIT"); return e && atoi(e) == 0; }();
+  if (off || P.tiles.empty() || g.n_heads % 8 != 0) return;
+  const int klen = P.cu_joint[P.tiles[0].seg + 1] - P.cu_joint[P.tiles[0].seg];
+  for (const AttnTile& t : P.tiles)
+    if (P.cu_joint[t.seg + 1] - P.cu_joint[t.seg] != klen) return;       // mixed lengths: longest-first order handles the tail
+  const int hpx = g.n_heads / 8, n_kt = (klen + 63) / 64;
+  const int slots = 32 * (P.qb == 128 ? 2 : 1);                            // workgroups one XCD holds at a time
+  const int per_xcd = (int)P.tiles.size() * hpx;
+  const int rem = per_xcd % slots;
+  if (per_xcd <= slots || rem == 0) return;
+  const int t_split = std::min((int)P.tiles.size(), (rem + hpx - 1) / hpx);     // blocks per head that make up the partial round
+  const int freed = (slots - (per_xcd - t_split * hpx) % slots) % slots;        // slots of the last full round the shares can use
+  int best_parts = 1; double best = 1.0;
+  for (int parts = 2; parts <= 4; ++parts) {
+    if (n_kt < 8 * parts) break;
+    const int items = t_split * hpx * parts - freed;
+    const double cost = (double)((items + slots - 1) / slots) / parts + 0.04;   // rounds of the split part (+ writing and adding the shares)
+    if (cost < best - 1e-9) { best = cost; best_parts = parts; }
+  }
+  if (best_parts == 1 || best > 0.75) return;      // (measured: 0.71 pays, -7 % attention time at 4250 tokens; 0.79 does not)
+  const int n_whole = (int)P.tiles.size() - t_split;
+  for (int i = 0; i < n_whole; ++i) P.tiles_split.push_back(P.tiles[i]);
+  for (int i = 0; i < t_split; ++i)
+    for (int pt = 0; pt < best_parts; ++pt) {
+      AttnTile t = P.tiles[n_whole + i];
+      t.kt0 = pt * n_kt / best_parts;
+      t.nkt = (pt + 1) * n_kt / best_parts - t.kt0;
+      t.parts = best_parts; t.part = pt; t.slot = i;
+      P.tiles_split.push_back(t);
+    }
+  P.split_slots = t_split; P.split_parts = best_parts;
+}
+
 void build_plan(const dit_ctx* c, int n_req, const dit_req* reqs, Plan& P) {
   const dit_config& g = c->cfg;
   P = Plan();
@@ -317,6 +360,7 @@ void build_plan(const dit_ctx* c, int n_req, const dit_req* reqs, Plan& P) {
   std::stable_sort(P.tiles.begin(), P.tiles.end(), [&](const AttnTile& a, const AttnTile& b) {
     return P.cu_joint[a.seg + 1] - P.cu_joint[a.seg] > P.cu_joint[b.seg + 1] - P.cu_joint[b.seg];
   });
+  plan_attention_split(P, g);
   std::vector<unsigned char>& m = P.meta;
   P.o_cu_txt = put(m, P.cu_txt); P.o_cu_img = put(m, P.cu_img); P.o_cu_joint = put(m, P.cu_joint);
   P.o_vt_off = put(m, P.vt_off); P.o_vtx_off = put(m, P.vtx_off); P.o_lat_off = put(m, P.lat_off);
@@ -328,6 +372,8 @@ void build_plan(const dit_ctx* c, int n_req, const dit_req* reqs, Plan& P) {
   P.o_tiles = put(m, P.tiles); P.o_xtiles = put(m, P.xtiles);
   P.o_txt_rows = put(m, txt_rows);
   P.o_vtcol_s = put(m, vtcol_s); P.o_vtcol_j = put(m, vtcol_j);
+  P.o_tiles_split = put(m, P.tiles_split);
+  P.o_split_cnt = put(m, std::vector<unsigned>((size_t)g.n_heads * P.split_slots + 1, 0u));   // (uploaded as zeros with every call)
   P.meta_bytes = rup(m.size(), 256);
   m.resize(P.meta_bytes);
 }
@@ -381,6 +427,7 @@ void layout_ws(const dit_ctx* c, const Plan& P, int max_steps, WsLayout& L) {
   L.yfin = take(Ni * (size_t)L.ldy * 4);
   L.rope = take((g.rope_axes[0] + g.rope_axes[1] + g.rope_axes[2]) > 0 ? Nj * (g.head_dim / 2) * 8 : 0);
   L.partial = take(GEMM_PARTIAL_BYTES);
+  L.attn_part = take((size_t)g.n_heads * P.split_slots * P.split_parts * P.qb * (g.head_dim + 1) * 4);   // sums of key-split attention blocks
   L.total = o;
 }
 
@@ -484,7 +531,7 @@ static float gmax(const dit_ctx* c, const std::string& a, const std::string& b =
 void run_attention(dit_ctx* c, const Run& R, const bf16_t* q, int ldq, const bf16_t* k, int ldk, const bf16_t* vt,
                    int ldvt, bf16_t* o, int ldo, const int* cu_q, const int* cu_k, const int* vt_off,
                    const AttnTile* tiles, int n_tiles, const int* o_row_map, double flop_units,
-                   float q_gain_max, float k_gain_max, const bf16_t* vt_lo = nullptr) {
+                   float q_gain_max, float k_gain_max, const bf16_t* vt_lo = nullptr, bool split = false) {
   const dit_config& g = c->cfg;
   AttnArgs a;
   a.q = q; a.ldq = ldq; a.k = k; a.ldk = ldk; a.vt = vt; a.ldvt = ldvt; a.o = o; a.ldo = ldo;
@@ -497,6 +544,11 @@ void run_attention(dit_ctx* c, const Run& R, const bf16_t* q, int ldq, const bf1
   const float logit_bound = a.scale_log2 * (float)g.head_dim * q_gain_max * k_gain_max * 1.02f;
   a.mode = logit_bound <= 60.0f ? 2 : 1;
   if (vt_lo) { a.mode = 4; a.vt_lo = vt_lo; }    // fp16 q/k, two-term values, running max
+  if (a.mode == 2 && split && R.P.split_slots > 0) {   // key-split blocks in the last round (they add without a running max)
+    a.tiles = (const AttnTile*)(R.ws + R.L.meta + R.P.o_tiles_split); a.n_tiles = (int)R.P.tiles_split.size();
+    a.hpx = g.n_heads / 8; a.n_slots = R.P.split_slots;
+    a.part = R.at<float>(R.L.attn_part); a.part_cnt = (unsigned*)(R.ws + R.L.meta + R.P.o_split_cnt);
+  }
   Scope sc(c, DIT_PROF_ATTN, flop_units * g.hidden, 0);
   launch_attention(c->stream, a);
 }
@@ -543,7 +595,7 @@ dit_status joint_block(dit_ctx* c, const Run& R, const std::string& p, const flo
   TAP(p + ".q", q, P.Nj, d, 2, d); TAP(p + ".k", k, P.Nj, d, 2, d);
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, o, d, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
                 (const AttnTile*)(R.ws + L.meta + P.o_tiles), (int)P.tiles.size(), R.ip(P.o_j2s), P.attn_flop,
-                gmax(c, pt + ".qnorm.g", pi + ".qnorm.g"), gmax(c, pt + ".knorm.g", pi + ".knorm.g"));
+                gmax(c, pt + ".qnorm.g", pi + ".qnorm.g"), gmax(c, pt + ".knorm.g", pi + ".knorm.g"), nullptr, true);
   TAP(p + ".attn", o, Ns, d, 2, d);   // stream order: text rows, then image rows
   run_gemm(c, {mk(o, d, Wm(c, pt + ".proj.w"), Wld(c, pt + ".proj.w"), Wv(c, pt + ".proj.b"), Nt, d, d, OUT_RESID_F32, x, d, mt + 2 * d, MC, rreq),
                mk(o + (size_t)Nt * d, d, Wm(c, pi + ".proj.w"), Wld(c, pi + ".proj.w"), Wv(c, pi + ".proj.b"), Ni, d, d, OUT_RESID_F32, x + (size_t)Nt * d, d, mi + 2 * d, MC, rreq + Nt)});
@@ -592,7 +644,7 @@ dit_status single_block(dit_ctx* c, const Run& R, const std::string& p, const fl
   }
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, cat, wide, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
                 (const AttnTile*)(R.ws + L.meta + P.o_tiles), (int)P.tiles.size(), nullptr, P.attn_flop,
-                gmax(c, p + ".qnorm.g"), gmax(c, p + ".knorm.g"));
+                gmax(c, p + ".qnorm.g"), gmax(c, p + ".knorm.g"), nullptr, true);
   TAP(p + ".attn", cat, Nj, d, 2, wide);
   run_gemm(c, {mk(cat, wide, Wm(c, p + ".lin2.w"), Wld(c, p + ".lin2.w"), Wv(c, p + ".lin2.b"), Nj, d, wide, OUT_RESID_F32, xj, d, m + 2 * d, MC, rreq)});
   TAP(p + ".x_out", xj, Nj, d, 4, d);
@@ -632,7 +684,7 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
   }
   run_attention(c, R, q, d, k, d, vt, P.Nv_pad, o, d, R.ip(P.o_cu_joint), R.ip(P.o_cu_joint), R.ip(P.o_vt_off),
                 (const AttnTile*)(R.ws + L.meta + P.o_tiles), (int)P.tiles.size(), nullptr, P.attn_flop,
-                gmax(c, p + ".qnorm.g"), gmax(c, p + ".knorm.g"));
+                gmax(c, p + ".qnorm.g"), gmax(c, p + ".knorm.g"), nullptr, true);
   TAP(p + ".attn", o, Ni, d, 2, d);
   run_gemm(c, {mk(o, d, Wm(c, p + ".proj.w"), Wld(c, p + ".proj.w"), Wv(c, p + ".proj.b"), Ni, d, d, OUT_RESID_F32, x, d, e + 2 * d, e6, rreq)});
   TAP(p + ".x_attn", x, Ni, d, 4, d);
@@ -943,6 +995,15 @@ size_t dit_workspace_bytes(const dit_ctx* c, int n_req, const dit_req* reqs, int
   build_plan(c, n_req, reqs, P);
   layout_ws(c, P, max_steps, L);
   return L.total;
+}
+
+dit_status dit_attention_plan(const dit_ctx* c, int n_req, const dit_req* reqs, int out[4]) {
+  if (!c || !out) return DIT_EINVAL;
+  if (validate_reqs(c, n_req, reqs) != DIT_OK) return DIT_ESHAPE;
+  Plan P;
+  build_plan(c, n_req, reqs, P);
+  out[0] = P.qb; out[1] = (int)P.tiles.size(); out[2] = P.split_slots; out[3] = P.split_parts;
+  return DIT_OK;
 }
 
 dit_status dit_bind(dit_ctx* c, void* w, size_t wb, void* ws, size_t wsb) {

@@ -72,7 +72,11 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile = 0);
 inline int gemm_stats_rows(int tile_code) { return (tile_code % 1000000) / 1000 / 2; }   // rows per stats chunk
 
 // ---- attention ----------------------------------------------------------------------
-struct AttnTile { int seg; int q0; };   // one block of q_per_tile queries of one segment
+// One block of q_per_tile queries of one segment.  parts == 0: against all keys of the segment.  parts > 0:
+// share `part` of `parts` of the key tiles, kt0 .. kt0 + nkt - 1 (tiles of 64 keys); the shares of one block
+// have the same `slot`, leave their unnormalised sums in AttnArgs::part and the last one to finish adds
+// them in the order of `part` and writes the output rows.
+struct AttnTile { int seg; int q0; int kt0; int nkt; int parts; int part; int slot; };
 int attn_q_per_tile(int longest_segment, int head_dim);   // 128 or 256 queries per workgroup
 struct AttnArgs {
   const bf16_t* q; int ldq;
@@ -93,6 +97,12 @@ struct AttnArgs {
   const float* bias = nullptr;  // mode 3: dev [n_heads][2*bias_L - 1]
   int bias_L = 0;               // mode 3: no segment is longer than this
   const bf16_t* vt_lo = nullptr; // mode 4: second term of the transposed values, same layout as vt
+  // Key-split blocks (mode 2 only: without a running max the shares of a block simply add).
+  int hpx = 0;                   // > 0: n_heads == 8 * hpx and workgroups run tile-major inside each group of hpx heads
+                                 // (one group per XCD), so that the shares, last in the tile list, are the tail of every XCD
+  int n_slots = 0;               // blocks that are split (AttnTile::slot < n_slots)
+  float* part = nullptr;         // dev [n_heads][n_slots][parts][q_per_tile * (head_dim + 1)] floats
+  unsigned* part_cnt = nullptr;  // dev [n_heads][n_slots], zero before the launch and zero again after it
 };
 void launch_attention(hipStream_t s, const AttnArgs& a);
 

@@ -70,6 +70,33 @@ def test_workspace_size_grows_with_batch_and_steps(B):
     wan.close()
 
 
+def test_attention_plan_splits_the_last_round_of_same_shape_blocks(B):
+    """Host arithmetic of the self-attention launch.  An XCD (32 CUs, 2 workgroups of 128 queries each per CU)
+    holds 64 workgroups at a time and owns n_heads/8 heads; blocks that would make a partly filled last round
+    are cut into key-split shares when that saves at least a quarter of a round."""
+    sd3 = B.DiT(synth.CONFIGS["sd3"]["arch"], bind=False)
+    # 4250 tokens: 34 blocks x 3 heads = 102 per XCD = 64 + 38: the last 13 blocks of every head in 3 shares
+    assert sd3.attention_plan(synth.make_requests("sd3")) == (128, 34, 13, 3)
+    assert sd3.attention_plan([(1, 104, 104, 112)]) == (128, 22, 1, 4)     # 66 per XCD: 2 over a round
+    assert sd3.attention_plan([(1, 96, 118, 112)]) == (128, 23, 2, 4)      # 69 per XCD: 5 over
+    assert sd3.attention_plan([(1, 128, 128, 154)] * 2) == (128, 68, 4, 4) # same-shape batch: 204 = 3 x 64 + 12
+    # 3 x 1146 tokens: 27 blocks per head, 81 per XCD; 18 key tiles per block allow two shares only (8 tiles each at least)
+    assert sd3.attention_plan([(1, 62, 64, 154)] * 3) == (128, 27, 6, 2)
+    assert sd3.attention_plan([(1, 32, 32, 154)])[2:] == (0, 1)            # 4 blocks: one round, nothing to split
+    assert sd3.attention_plan([(1, 96, 192, 154)])[2:] == (0, 1)           # 114 per XCD: 50 over, no share count pays
+    assert sd3.attention_plan(synth.make_requests("hetero8"))[2:] == (0, 1)   # mixed shapes: longest-first order instead
+    sd3.close()
+    flux = B.DiT(synth.CONFIGS["flux"]["arch"], bind=False)
+    assert flux.attention_plan(synth.make_requests("flux")) == (128, 36, 0, 1)    # 108 per XCD: 4 shares would cost 0.79 rounds
+    flux.close()
+    wan = B.DiT(synth.CONFIGS["wan"]["arch"], bind=False)
+    assert wan.attention_plan(synth.make_requests("wan")) == (256, 128, 0, 1)     # 640 per XCD = 20 full rounds of 32
+    wan.close()
+    tiny = B.DiT(synth.CONFIGS["tiny"]["arch"], bind=False)
+    assert tiny.attention_plan([(1, 256, 256, 16)])[2:] == (0, 1)          # head count not a multiple of 8
+    tiny.close()
+
+
 def test_create_rejects_bad_configurations(B):
     base = synth.CONFIGS["tiny"]["arch"]
     def status(**kw):
