@@ -841,8 +841,9 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     }
   }
   if (!tile) {
-    // One round of 256x128 tiles (8 waves, 3-stage ring) when that fits the chip and K is long:
-    // a workgroup per CU with three slabs in flight, against 1.6 128x128 workgroups per CU.
+    // One round of 256x128 tiles (8 waves, 3-stage ring) when that fits the chip and K is not short:
+    // a workgroup per CU with three slabs in flight, against 1.6 128x128 workgroups per CU (measured on the
+    // 4250-row request: 7 % faster at K = 6144, 3 % at K = 1536).
     long long t21 = 0;
     int min_k = 1 << 30;
     bool plain = true;
@@ -852,7 +853,7 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
       min_k = b.p[i].K < min_k ? b.p[i].K : min_k;
       plain = plain && b.p[i].out_kind != OUT_QKNORM && b.p[i].conv_w <= 0;
     }
-    if (plain && t21 > 128 && t21 <= 256 && min_k >= 4096) tile = 32256128;
+    if (plain && t21 > 128 && t21 <= 256 && min_k >= 1536) tile = 32256128;
   }
   if (!tile) {
     int max_n = 0;
@@ -866,14 +867,19 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
       t256 += (long long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
     const long long rem = t256 % 256;
     tile = (t256 >= 1024 || (t256 >= 256 && (rem == 0 || rem >= 64))) ? 1256256 : 128128;
-    // A 320-row tile when it turns two rounds into one: the 4250-row QKV product of the 1024^2 request is
-    // 306 tiles of 256x256 (a second round for 50 tiles) but 252 of 320x256, one round of tiles 1.25 times
-    // as long (measured 56 us against 71 us with 128x128 tiles and 77 us with 256x256).
-    if (t256 > 256 && t256 <= 320) {
+    // A 320-row tile when it saves rounds: the 4250-row QKV product of the 1024^2 request is 306 tiles of
+    // 256x256 (a second round for 50 tiles) but 252 of 320x256, one round of tiles 1.25 times as long (measured
+    // 56 us against 71 us with 128x128 tiles and 77 us with 256x256); 864 tiles (4 rounds) against 720 (3 rounds
+    // x 1.25) measured 5 % faster.  Per unit of work the two tiles are equally fast at K <= 5120, so the rule is
+    // rounds alone, with a margin.
+    bool any_conv = false;                  // (convolutions have no 320-row instantiation)
+    for (int i = 0; i < b.n; ++i) any_conv = any_conv || b.p[i].conv_w > 0;
+    if (t256 > 256 && !any_conv) {
       long long t320 = 0;
       for (int i = 0; i < b.n; ++i)
         t320 += (long long)((b.p[i].M + 319) / 320) * ((b.p[i].N + 255) / 256);
-      if (t320 <= 256) tile = 1320256;
+      const long long r256 = (t256 + 255) / 256, r320 = (t320 + 255) / 256;
+      if (125 * r320 <= 95 * r256) tile = 1320256;
     }
   }
   bool conv = false, plain = false, qknorm = false;
