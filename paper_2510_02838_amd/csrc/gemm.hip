@@ -807,6 +807,7 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
 //             (default: k-slab 64, 2 stages)
 //   31256128 / 32256128 / 31128256  256x128 (4 waves / 8 waves) and 128x256 with a 3-stage ring
 //   30128128  128x128, k-slab 64, 4-stage ring (one workgroup per CU: for grids below 256 tiles)
+//   30128064 / 33128064  128x64 (4 waves of 32x64), 6- / 3-stage ring
 //   40128128  the same as split-K over b.splits shares of K plus the reduction kernel
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
   // Tile choice.  The 256x256 tile (8 waves) halves the L2->LDS traffic per flop of the 128x128
@@ -837,7 +838,18 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
       bool qk = false;                       // the reduction kernel has no q/k-norm epilogue
       for (int i = 0; i < b.n; ++i) qk = qk || b.p[i].out_kind == OUT_QKNORM || b.p[i].conv_w > 0;   // (nor the split A offsets a convolution's)
       if (b.partial && sp >= 2 && !qk) { b.splits = (int)sp; tile = 40128128; }
-      else tile = 30128128;
+      else {
+        // no split (q/k-norm epilogue, or K too short): 128x64 tiles with a 6-stage ring when twice the
+        // workgroups still fit one round: these launches run at memory latency, and twice as many CUs with
+        // more bytes in flight each fetch the weights faster (108 -> 216 workgroups: 17.4 -> 13.2 us)
+        long long t64 = 0;
+        for (int i = 0; i < b.n; ++i)
+          if (b.p[i].M > 0 && b.p[i].N > 0) t64 += (long long)((b.p[i].M + 127) / 128) * ((b.p[i].N + 63) / 64);
+        bool narrow_ok = true;        // not for convolutions; a 128-wide head must lie inside one workgroup's columns
+        for (int i = 0; i < b.n; ++i)
+          narrow_ok = narrow_ok && b.p[i].conv_w <= 0 && !(b.p[i].out_kind == OUT_QKNORM && b.p[i].qk.head_dim > 64);
+        tile = (t64 <= 256 && narrow_ok) ? 30128064 : 30128128;
+      }
     }
   }
   if (!tile) {
@@ -889,8 +901,11 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
   }
   // the q/k-norm epilogue exists only in the instantiations whose waves own 64 output columns
   if (qknorm && !(tile == 1256256 || tile == 1320256 || tile == 11256256 || tile == 21256256 || tile == 128128 || tile == 10128128 ||
-                  tile == 30128128 || tile == 256128 || tile == 31256128 || tile == 32256128))
+                  tile == 30128128 || tile == 30128064 || tile == 33128064 || tile == 256128 || tile == 31256128 || tile == 32256128))
     return -1;
+  if (qknorm && (tile == 30128064 || tile == 33128064))      // 64 columns per workgroup: heads of 64 only
+    for (int i = 0; i < b.n; ++i)
+      if (b.p[i].out_kind == OUT_QKNORM && b.p[i].qk.head_dim > 64) return -1;
   if (conv) {     // convolutions: never mixed with plain products, three tile shapes
     if (plain) return -1;
     for (int i = 0; i < b.n; ++i)        // whole images of whole rows
@@ -912,6 +927,8 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     case 128256: launch_t<128, 256, 2, 2, 64, 2, 0, false, 2>(s, b); break;
     case 10128128: launch_t<128, 128, 2, 2, 32, 4, 0, false, 2>(s, b); break;
     case 30128128: launch_t<128, 128, 2, 2, 64, 4, 0, false, 2>(s, b); break;
+    case 30128064: launch_t<128, 64, 4, 1, 64, 6, 0, false, 2>(s, b); break;
+    case 33128064: launch_t<128, 64, 4, 1, 64, 3, 0, false, 2>(s, b); break;
     case 31256128: launch_t<256, 128, 2, 2, 64, 3, 0, false, 2>(s, b); break;
     case 32256128: launch_t<256, 128, 4, 2, 64, 3, 0, false, 2>(s, b); break;
     case 31128256: launch_t<128, 256, 2, 2, 64, 3, 0, false, 2>(s, b); break;
