@@ -132,10 +132,12 @@ void launch_v_transpose(hipStream_t s, const bf16_t* v, int ld, int v_col_off, i
 
 void launch_latent_update(hipStream_t s, float* x, const float* v, long long n, float a, float b);
 
-// y[m][n] = sum_k f(x[m][k]) W[n][k] + b[n] (+ add[(m % add_mod)][n]); f = SiLU if silu_in.
-// x fp32 [M][ldx], W bf16 [N][ldw], y fp32 [M][ldy].
-void launch_skinny(hipStream_t s, const float* x, int ldx, const bf16_t* W, int ldw,
-                   const float* bias, float* y, int ldy, int M, int N, int K, int silu_in);
+// y[m][out_off_j + n] = sum_k f(x[m][k]) W_j[n][k] + b_j[n] for a device table of matrices sharing x (few rows
+// M: one launch reads every matrix once); f = SiLU if silu_in.  x fp32 [M][ldx], W_j bf16 [N_j][ldw_j], y fp32
+// [M][ldy].  Needs K % 8 == 0, ldx % 4 == 0, ldw_j % 8 == 0; returns false (nothing launched) otherwise.
+struct SkinnyMat { const bf16_t* W; const float* bias; int N, ldw, out_off, pad; };
+bool launch_skinny(hipStream_t s, const float* x, int ldx, const SkinnyMat* dev_mats, int n_mats, int max_n,
+                   float* y, int ldy, int M, int K, int silu_in);
 
 void launch_timestep_features(hipStream_t s, const float* sigma_dev, float* out, int M);
 void launch_silu_split(hipStream_t s, const float* x, bf16_t* hi, bf16_t* lo, long long n, int silu = 1);   // hi + lo = SiLU(x) or x

@@ -228,48 +228,79 @@ void launch_latent_update(hipStream_t s, float* x, const float* v, long long n, 
 }
 
 // ---------------------------------------------------------------------------------------
-// small-M product  y[m][n] = sum_k f(x[m][k]) W[n][k] + bias[n]   (fp32 x, bf16 W, fp32 y)
-// one wave per output column n, 8 rows of x at a time; W is read once per 8 rows.
+// small-M products  y[m][off_j + n] = sum_k f(x[m][k]) W_j[n][k] + bias_j[n]   (fp32 x, bf16 W, fp32 y)
+// for a table of matrices W_j that share x: the conditioning vectors of a few (step, request) rows against
+// the timestep MLP and the modulation matrices of every block (1.4 GB of weights at hidden 1536, read once).
+// Grid (column groups, matrix).  A workgroup stages f(x) for up to MR rows in LDS once (SiLU included) and
+// owns 32 columns, 8 per wave; a lane reads 16 bytes of a weight row per pass over K and the matching two
+// 16-byte pieces of every staged row (even and odd pieces are kept in separate halves of the staged row, so
+// that the lanes of a wave read consecutive LDS addresses).
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ float silu_f(float x) { return x / (1.f + __expf(-x)); }
 
-__global__ __launch_bounds__(256) void skinny_kernel(const float* __restrict__ x, int ldx,
-                                                     const bf16_t* __restrict__ W, int ldw,
-                                                     const float* __restrict__ bias, float* __restrict__ y, int ldy,
-                                                     int M, int N, int K, int silu_in) {
-  const int n = blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (n >= N) return;
-  const int lane = threadIdx.x & 63;
-  const bf16_t* wr = W + (size_t)n * ldw;
-  for (int m0 = 0; m0 < M; m0 += 8) {
-    float acc[8];
+template <int MR>
+__global__ __launch_bounds__(256) void skinny_kernel(const float* __restrict__ x, int ldx, const SkinnyMat* __restrict__ mats,
+                                                     float* __restrict__ y, int ldy, int M, int K, int silu_in) {
+  extern __shared__ __attribute__((aligned(16))) float xs[];          // [MR][K]
+  const SkinnyMat mt = mats[blockIdx.y];
+  if ((int)blockIdx.x * 32 >= mt.N) return;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int n0 = blockIdx.x * 32 + wave * 8;
+  const int KH = K >> 1;                                               // floats in the half that holds the even pieces
+  for (int m0 = 0; m0 < M; m0 += MR) {
+    const int rows = M - m0 < MR ? M - m0 : MR;
+    __syncthreads();
+    for (int idx = threadIdx.x * 4; idx < rows * K; idx += 1024) {
+      const int r = idx / K, k = idx - r * K, q = k >> 2;
+      float4 v = *(const float4*)(x + (size_t)(m0 + r) * ldx + k);
+      if (silu_in) { v.x = silu_f(v.x); v.y = silu_f(v.y); v.z = silu_f(v.z); v.w = silu_f(v.w); }
+      *(float4*)(xs + r * K + (q & 1) * KH + (q >> 1) * 4) = v;
+    }
+    __syncthreads();
+    for (int c = 0; c < 8; ++c) {
+      const int n = n0 + c;
+      if (n >= mt.N) break;
+      const bf16_t* wr = mt.W + (size_t)n * mt.ldw;
+      float acc[MR];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-    for (int k = lane * 4; k < K; k += 256) {
-      const uint2 wraw = *(const uint2*)(wr + k);
-      const float w0 = bf2f((uint16_t)(wraw.x & 0xFFFF)), w1 = bf2f((uint16_t)(wraw.x >> 16));
-      const float w2 = bf2f((uint16_t)(wraw.y & 0xFFFF)), w3 = bf2f((uint16_t)(wraw.y >> 16));
+      for (int i = 0; i < MR; ++i) acc[i] = 0.f;
+      for (int k = lane * 8; k < K; k += 512) {
+        const uint4 wraw = *(const uint4*)(wr + k);
+        const float w0 = bf2f((uint16_t)(wraw.x & 0xFFFF)), w1 = bf2f((uint16_t)(wraw.x >> 16));
+        const float w2 = bf2f((uint16_t)(wraw.y & 0xFFFF)), w3 = bf2f((uint16_t)(wraw.y >> 16));
+        const float w4 = bf2f((uint16_t)(wraw.z & 0xFFFF)), w5 = bf2f((uint16_t)(wraw.z >> 16));
+        const float w6 = bf2f((uint16_t)(wraw.w & 0xFFFF)), w7 = bf2f((uint16_t)(wraw.w >> 16));
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
-        if (m0 + i < M) {
-          float4 xv = *(const float4*)(x + (size_t)(m0 + i) * ldx + k);
-          if (silu_in) { xv.x = silu_f(xv.x); xv.y = silu_f(xv.y); xv.z = silu_f(xv.z); xv.w = silu_f(xv.w); }
-          acc[i] += (xv.x * w0 + xv.y * w1) + (xv.z * w2 + xv.w * w3);
+        for (int i = 0; i < MR; ++i) {
+          if (i < rows) {
+            const float4 xa = *(const float4*)(xs + i * K + (k >> 1)), xb = *(const float4*)(xs + i * K + KH + (k >> 1));
+            acc[i] += ((xa.x * w0 + xa.y * w1) + (xa.z * w2 + xa.w * w3)) + ((xb.x * w4 + xb.y * w5) + (xb.z * w6 + xb.w * w7));
+          }
         }
       }
-    }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float t = wave_sum(acc[i]);
-      if (lane == 0 && m0 + i < M) y[(size_t)(m0 + i) * ldy + n] = t + (bias ? bias[n] : 0.f);
+      for (int i = 0; i < MR; ++i) {
+        if (i < rows) {
+          const float t = wave_sum(acc[i]);
+          if (lane == 0) y[(size_t)(m0 + i) * ldy + mt.out_off + n] = t + (mt.bias ? mt.bias[n] : 0.f);
+        }
+      }
     }
   }
 }
 
-void launch_skinny(hipStream_t s, const float* x, int ldx, const bf16_t* W, int ldw, const float* bias, float* y,
-                   int ldy, int M, int N, int K, int silu_in) {
-  if (M == 0 || N == 0) return;
-  hipLaunchKernelGGL(skinny_kernel, dim3((N + 3) / 4), dim3(256), 0, s, x, ldx, W, ldw, bias, y, ldy, M, N, K, silu_in);
+// K a multiple of 8, ldx a multiple of 4, every ldw a multiple of 8; returns false when the shape is not one it takes
+bool launch_skinny(hipStream_t s, const float* x, int ldx, const SkinnyMat* dev_mats, int n_mats, int max_n, float* y,
+                   int ldy, int M, int K, int silu_in) {
+  if (M == 0 || n_mats == 0 || max_n == 0) return true;
+  if (K % 8 || ldx % 4 || K > 16384) return false;
+  const dim3 g((max_n + 31) / 32, n_mats), b(256);
+  // rows staged at a time: as many as 64 KB of LDS hold
+  if (K <= 2048) hipLaunchKernelGGL(skinny_kernel<8>, g, b, (size_t)8 * K * 4, s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
+  else if (K <= 4096) hipLaunchKernelGGL(skinny_kernel<4>, g, b, (size_t)4 * K * 4, s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
+  else if (K <= 8192) hipLaunchKernelGGL(skinny_kernel<2>, g, b, (size_t)2 * K * 4, s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
+  else hipLaunchKernelGGL(skinny_kernel<1>, g, b, (size_t)K * 4, s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
+  return true;
 }
 
 // hi + lo = SiLU(x) (or x itself) as two bf16 terms (about 16 mantissa bits), for feeding an MFMA GEMM
