@@ -257,32 +257,50 @@ __global__ __launch_bounds__(256) void skinny_kernel(const float* __restrict__ x
       *(float4*)(xs + r * K + (q & 1) * KH + (q >> 1) * 4) = v;
     }
     __syncthreads();
-    for (int c = 0; c < 8; ++c) {
-      const int n = n0 + c;
-      if (n >= mt.N) break;
-      const bf16_t* wr = mt.W + (size_t)n * mt.ldw;
-      float acc[MR];
+    // four columns at a time: each staged piece is read once for four weight rows, and a lane has four
+    // 16-byte weight loads in flight (these products run at memory latency)
+    for (int c = 0; c < 8; c += 4) {
+      if (n0 + c >= mt.N) break;
+      const bf16_t* wr[4];
 #pragma unroll
-      for (int i = 0; i < MR; ++i) acc[i] = 0.f;
+      for (int j = 0; j < 4; ++j) wr[j] = mt.W + (size_t)(n0 + c + j < mt.N ? n0 + c + j : mt.N - 1) * mt.ldw;
+      float acc[MR][4];
+#pragma unroll
+      for (int i = 0; i < MR; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
       for (int k = lane * 8; k < K; k += 512) {
-        const uint4 wraw = *(const uint4*)(wr + k);
-        const float w0 = bf2f((uint16_t)(wraw.x & 0xFFFF)), w1 = bf2f((uint16_t)(wraw.x >> 16));
-        const float w2 = bf2f((uint16_t)(wraw.y & 0xFFFF)), w3 = bf2f((uint16_t)(wraw.y >> 16));
-        const float w4 = bf2f((uint16_t)(wraw.z & 0xFFFF)), w5 = bf2f((uint16_t)(wraw.z >> 16));
-        const float w6 = bf2f((uint16_t)(wraw.w & 0xFFFF)), w7 = bf2f((uint16_t)(wraw.w >> 16));
+        uint4 wraw[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) wraw[j] = *(const uint4*)(wr[j] + k);
+        float w[4][8];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          w[j][0] = bf2f((uint16_t)(wraw[j].x & 0xFFFF)); w[j][1] = bf2f((uint16_t)(wraw[j].x >> 16));
+          w[j][2] = bf2f((uint16_t)(wraw[j].y & 0xFFFF)); w[j][3] = bf2f((uint16_t)(wraw[j].y >> 16));
+          w[j][4] = bf2f((uint16_t)(wraw[j].z & 0xFFFF)); w[j][5] = bf2f((uint16_t)(wraw[j].z >> 16));
+          w[j][6] = bf2f((uint16_t)(wraw[j].w & 0xFFFF)); w[j][7] = bf2f((uint16_t)(wraw[j].w >> 16));
+        }
 #pragma unroll
         for (int i = 0; i < MR; ++i) {
           if (i < rows) {
             const float4 xa = *(const float4*)(xs + i * K + (k >> 1)), xb = *(const float4*)(xs + i * K + KH + (k >> 1));
-            acc[i] += ((xa.x * w0 + xa.y * w1) + (xa.z * w2 + xa.w * w3)) + ((xb.x * w4 + xb.y * w5) + (xb.z * w6 + xb.w * w7));
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+              acc[i][j] += ((xa.x * w[j][0] + xa.y * w[j][1]) + (xa.z * w[j][2] + xa.w * w[j][3])) +
+                           ((xb.x * w[j][4] + xb.y * w[j][5]) + (xb.z * w[j][6] + xb.w * w[j][7]));
           }
         }
       }
 #pragma unroll
       for (int i = 0; i < MR; ++i) {
         if (i < rows) {
-          const float t = wave_sum(acc[i]);
-          if (lane == 0) y[(size_t)(m0 + i) * ldy + mt.out_off + n] = t + (mt.bias ? mt.bias[n] : 0.f);
+#pragma unroll
+          for (int j = 0; j < 4; ++j) {
+            const float t = wave_sum(acc[i][j]);
+            const int n = n0 + c + j;
+            if (lane == 0 && n < mt.N) y[(size_t)(m0 + i) * ldy + mt.out_off + n] = t + (mt.bias ? mt.bias[n] : 0.f);
+          }
         }
       }
     }
@@ -295,11 +313,12 @@ bool launch_skinny(hipStream_t s, const float* x, int ldx, const SkinnyMat* dev_
   if (M == 0 || n_mats == 0 || max_n == 0) return true;
   if (K % 8 || ldx % 4 || K > 16384) return false;
   const dim3 g((max_n + 31) / 32, n_mats), b(256);
-  // rows staged at a time: as many as 64 KB of LDS hold
-  if (K <= 2048) hipLaunchKernelGGL(skinny_kernel<8>, g, b, (size_t)8 * K * 4, s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
-  else if (K <= 4096) hipLaunchKernelGGL(skinny_kernel<4>, g, b, (size_t)4 * K * 4, s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
-  else if (K <= 8192) hipLaunchKernelGGL(skinny_kernel<2>, g, b, (size_t)2 * K * 4, s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
-  else hipLaunchKernelGGL(skinny_kernel<1>, g, b, (size_t)K * 4, s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
+  // rows staged at a time: as many as 64 KB of LDS hold (fewer rows, less LDS, more workgroups per CU)
+  auto lds = [&](int mr) { return (size_t)(M < mr ? M : mr) * K * 4; };
+  if (K <= 2048) hipLaunchKernelGGL(skinny_kernel<8>, g, b, lds(8), s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
+  else if (K <= 4096) hipLaunchKernelGGL(skinny_kernel<4>, g, b, lds(4), s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
+  else if (K <= 8192) hipLaunchKernelGGL(skinny_kernel<2>, g, b, lds(2), s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
+  else hipLaunchKernelGGL(skinny_kernel<1>, g, b, lds(1), s, x, ldx, dev_mats, y, ldy, M, K, silu_in);
   return true;
 }
 
