@@ -807,7 +807,7 @@ static void launch_t(hipStream_t s, GemmBatch& b) {
 //             (default: k-slab 64, 2 stages)
 //   31256128 / 32256128 / 31128256  256x128 (4 waves / 8 waves) and 128x256 with a 3-stage ring
 //   30128128  128x128, k-slab 64, 4-stage ring (one workgroup per CU: for grids below 256 tiles)
-//   30128064 / 33128064  128x64 (4 waves of 32x64), 6- / 3-stage ring
+//   30128064 / 33128064  128x64 (4 waves of 32x64), 6- / 3-stage ring;  30064128  64x128 (4 waves of 64x32), 6-stage ring
 //   40128128  the same as split-K over b.splits shares of K plus the reduction kernel
 int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
   // Tile choice.  The 256x256 tile (8 waves) halves the L2->LDS traffic per flop of the 128x128
@@ -849,6 +849,15 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
         for (int i = 0; i < b.n; ++i)
           narrow_ok = narrow_ok && b.p[i].conv_w <= 0 && !(b.p[i].out_kind == OUT_QKNORM && b.p[i].qk.head_dim > 64);
         tile = (t64 <= 256 && narrow_ok) ? 30128064 : 30128128;
+        if (tile == 30128128 && !qk) {          // ... or 64-row tiles when that gives more workgroups in one round
+          long long t6 = 0;
+          bool plain = true;
+          for (int i = 0; i < b.n; ++i) {
+            if (b.p[i].M > 0 && b.p[i].N > 0) t6 += (long long)((b.p[i].M + 63) / 64) * ((b.p[i].N + 127) / 128);
+            plain = plain && b.p[i].conv_w <= 0;
+          }
+          if (plain && t6 <= 256 && t6 > t128) tile = 30064128;
+        }
       }
     }
   }
@@ -928,6 +937,7 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     case 10128128: launch_t<128, 128, 2, 2, 32, 4, 0, false, 2>(s, b); break;
     case 30128128: launch_t<128, 128, 2, 2, 64, 4, 0, false, 2>(s, b); break;
     case 30128064: launch_t<128, 64, 4, 1, 64, 6, 0, false, 2>(s, b); break;
+    case 30064128: launch_t<64, 128, 1, 4, 64, 6, 0, false, 2>(s, b); break;
     case 33128064: launch_t<128, 64, 4, 1, 64, 3, 0, false, 2>(s, b); break;
     case 31256128: launch_t<256, 128, 2, 2, 64, 3, 0, false, 2>(s, b); break;
     case 32256128: launch_t<256, 128, 4, 2, 64, 3, 0, false, 2>(s, b); break;

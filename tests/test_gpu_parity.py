@@ -67,7 +67,7 @@ def test_set_get_tensor_round_trip(torch, B):
 
 # ---------------------------------------------------------------------------------- GEMM
 @pytest.mark.parametrize("M,N,K", [(300, 384, 256), (1, 256, 64), (517, 1000, 192), (4250, 1536, 1536)])
-@pytest.mark.parametrize("variant", [0, 128128, 10128128, 30128128, 30128064, 33128064, 256256, 1256256, 1320256, 10256256, 11256256, 20256256, 21256256,
+@pytest.mark.parametrize("variant", [0, 128128, 10128128, 30128128, 30128064, 33128064, 30064128, 256256, 1256256, 1320256, 10256256, 11256256, 20256256, 21256256,
                                      256128, 128256, 31256128, 32256128, 31128256])
 def test_gemm_against_float64_matmul(torch, B, M, N, K, variant):
     if M > 1000 and variant not in (0, 1256256, 1320256, 11256256, 128128, 32256128):
