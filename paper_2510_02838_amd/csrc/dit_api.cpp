@@ -67,7 +67,7 @@ struct Plan {
 };
 
 struct WsLayout {
-  size_t meta, sig, coef_a, coef_b, feat, th1, vec, mhi, mlo, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, vtx, vtlo, o, act, cproj,
+  size_t meta, sig, coef_a, coef_b, feat, th1, vec, mhi, mlo, mod, modblk, x, xj, xt0, h, qkv, q, k, vt, xk, vtx, vtlo, o, act, cproj,
       patch, yfin, rope, partial, attn_part, total;
   int MC = 0;        // modulation columns per conditioning row
   int R = 0;         // conditioning rows = steps * n_req
@@ -421,8 +421,12 @@ void layout_ws(const dit_ctx* c, const Plan& P, int max_steps, WsLayout& L) {
   L.q = take(Nj * d * 2);
   L.k = take(std::max(Nj, Nt) * d * 2);
   L.vt = take(d * (size_t)P.Nv_pad * 2);         // self-attention values, transposed (pad columns stay zero for a whole call)
-  L.vtx = take(g.family == DIT_FAMILY_W ? d * (size_t)P.Nvx_pad * 2 : 0);    // cross-attention values: first ...
-  L.vtlo = take(g.family == DIT_FAMILY_W ? d * (size_t)P.Nvx_pad * 2 : 0);   // ... and second term
+  // cross-attention keys (fp16) and transposed values (two bf16 terms) of EVERY block: they depend on the condition
+  // only and are formed once per call, not once per step
+  const size_t nbw = g.family == DIT_FAMILY_W ? (size_t)g.n_blocks : 0;
+  L.xk = take(nbw * Nt * d * 2);
+  L.vtx = take(nbw * d * (size_t)P.Nvx_pad * 2);     // first ...
+  L.vtlo = take(nbw * d * (size_t)P.Nvx_pad * 2);    // ... and second term
   L.o = take(Ns * d * 2);
   L.act = take(std::max(std::max(Ns * dff, Nj * wide) * 2, Nt * 2 * d * 4));    // (family W: fp32 keys|values of the condition)
   L.cproj = take(g.family == DIT_FAMILY_W ? Nt * d * 2 * 2 : 0);               // projected condition as two bf16 terms
@@ -655,7 +659,27 @@ dit_status single_block(dit_ctx* c, const Run& R, const std::string& p, const fl
 }
 
 // self-attention + cross-attention + MLP block of family W (image rows only in x)
-dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* base) {
+// Keys and values of block `blk`'s cross-attention, from the two-term projected condition with fp32 results:
+// keys RMS-normalised per head and stored as fp16, values transposed as two bf16 terms.  Step-invariant.
+dit_status w_cross_kv(dit_ctx* c, const Run& R, const std::string& p, int blk) {
+  const dit_config& g = c->cfg;
+  const Plan& P = R.P; const WsLayout& L = R.L;
+  const int d = g.hidden, Nt = P.Nt;
+  if (!(gmax(c, p + ".xqnorm.g") <= 1024.f && gmax(c, p + ".xknorm.g") <= 1024.f))
+    return fail(c, DIT_EUNSUPPORTED, "%s: cross-attention norm gains above 1024 do not fit the fp16 storage of its queries and keys", p.c_str());
+  const bf16_t* cproj = R.at<bf16_t>(L.cproj);
+  const bf16_t* cproj_lo = cproj + (size_t)Nt * d;
+  float* kv32 = R.at<float>(L.act);
+  run_gemm(c, {mk(cproj, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), Wv(c, p + ".xkv.b"), Nt, 2 * d, d, OUT_F32, kv32, 2 * d)});
+  run_gemm(c, {mk(cproj_lo, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), nullptr, Nt, 2 * d, d, OUT_RESID_F32, kv32, 2 * d)});
+  Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Nt * d);
+  launch_cross_kv_finish(c->stream, kv32, 2 * d, Nt, g.n_heads, g.head_dim, Wv(c, p + ".xknorm.g"),
+                         R.at<bf16_t>(L.xk) + (size_t)blk * Nt * d, d, R.ip(P.o_src_of_col_x), P.Nvx_pad,
+                         R.at<bf16_t>(L.vtx) + (size_t)blk * d * P.Nvx_pad, R.at<bf16_t>(L.vtlo) + (size_t)blk * d * P.Nvx_pad, P.Nvx_pad);
+  return DIT_OK;
+}
+
+dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* base, int blk) {
   const dit_config& g = c->cfg;
   const Plan& P = R.P; const WsLayout& L = R.L;
   const int d = g.hidden, dff = g.mlp_hidden, Ni = P.Ni, Nt = P.Nt, e6 = 6 * d;
@@ -663,7 +687,7 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
   float* e = R.at<float>(L.modblk);
   bf16_t* h = R.at<bf16_t>(L.h); bf16_t* qkv = R.at<bf16_t>(L.qkv);
   bf16_t* q = R.at<bf16_t>(L.q); bf16_t* k = R.at<bf16_t>(L.k); bf16_t* vt = R.at<bf16_t>(L.vt);
-  bf16_t* o = R.at<bf16_t>(L.o); bf16_t* act = R.at<bf16_t>(L.act); bf16_t* cproj = R.at<bf16_t>(L.cproj);
+  bf16_t* o = R.at<bf16_t>(L.o); bf16_t* act = R.at<bf16_t>(L.act);
   const int* rreq = R.ip(P.o_row_req_s);
   const float2* rope = (g.rope_axes[0] + g.rope_axes[1] + g.rope_axes[2]) > 0 ? R.at<float2>(L.rope) : nullptr;
   {
@@ -698,26 +722,17 @@ dit_status w_block(dit_ctx* c, const Run& R, const std::string& p, const float* 
   }
   // The cross-attention output enters the residual stream without a gate, so its rounding noise is
   // not damped as that of the gated branches is: queries and keys are stored as fp16 (both are
-  // RMS-normalised, hence bounded), the condition's keys and values are formed from the two-term
-  // projected condition with fp32 results, and the values go to the attention as two bf16 terms.
-  // (Always the product's epilogue: there is no capture point between it and the attention.)
-  if (!(gmax(c, p + ".xqnorm.g") <= 1024.f && gmax(c, p + ".xknorm.g") <= 1024.f))
-    return fail(c, DIT_EUNSUPPORTED, "%s: cross-attention norm gains above 1024 do not fit the fp16 storage of its queries and keys", p.c_str());
+  // RMS-normalised, hence bounded) and the values go to the attention as two bf16 terms; keys and
+  // values come from w_cross_kv below, once per call.
+  // (The q/k norm is always the product's epilogue: there is no capture point between it and the attention.)
   GemmProblem pxq = with_qknorm(mk(h, d, Wm(c, p + ".xq.w"), Wld(c, p + ".xq.w"), Wv(c, p + ".xq.b"), Ni, d, d, OUT_BF16, qkv, d),
                                 d, 0, g.head_dim, Wv(c, p + ".xqnorm.g"), nullptr, nullptr, nullptr, q, nullptr, d, qs);
   pxq.qk.f16 = 1;
-  float* kv32 = R.at<float>(L.act);
-  bf16_t* cproj_lo = cproj + (size_t)Nt * d;
-  bf16_t* vtx = R.at<bf16_t>(L.vtx);
-  bf16_t* vtlo = R.at<bf16_t>(L.vtlo);
-  run_gemm(c, {pxq, mk(cproj, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), Wv(c, p + ".xkv.b"), Nt, 2 * d, d, OUT_F32, kv32, 2 * d)});
-  run_gemm(c, {mk(cproj_lo, d, Wm(c, p + ".xkv.w"), Wld(c, p + ".xkv.w"), nullptr, Nt, 2 * d, d, OUT_RESID_F32, kv32, 2 * d)});
-  {
-    Scope sc(c, DIT_PROF_QKNORM, 0, 12.0 * Nt * d);
-    launch_cross_kv_finish(c->stream, kv32, 2 * d, Nt, g.n_heads, g.head_dim, Wv(c, p + ".xknorm.g"), k, d,
-                           R.ip(P.o_src_of_col_x), P.Nvx_pad, vtx, vtlo, P.Nvx_pad);
-  }
-  run_attention(c, R, q, d, k, d, vtx, P.Nvx_pad, o, d, R.ip(P.o_cu_img), R.ip(P.o_cu_txt), R.ip(P.o_vtx_off),
+  const bf16_t* xk = R.at<bf16_t>(L.xk) + (size_t)blk * Nt * d;
+  const bf16_t* vtx = R.at<bf16_t>(L.vtx) + (size_t)blk * d * P.Nvx_pad;
+  const bf16_t* vtlo = R.at<bf16_t>(L.vtlo) + (size_t)blk * d * P.Nvx_pad;
+  run_gemm(c, {pxq});
+  run_attention(c, R, q, d, xk, d, vtx, P.Nvx_pad, o, d, R.ip(P.o_cu_img), R.ip(P.o_cu_txt), R.ip(P.o_vtx_off),
                 (const AttnTile*)(R.ws + L.meta + P.o_xtiles), (int)P.xtiles.size(), nullptr, P.xattn_flop,
                 gmax(c, p + ".xqnorm.g"), gmax(c, p + ".xknorm.g"), vtlo);
   TAP(p + ".xattn", o, Ni, d, 2, d);
@@ -881,6 +896,11 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
     Scope sc(c, DIT_PROF_OTHER, 0, 0);
     launch_silu_split(s, R.at<float>(L.xt0), R.at<bf16_t>(L.cproj), R.at<bf16_t>(L.cproj) + (size_t)Nt * d, (long long)Nt * d, 0);
   }
+  if (g.family == DIT_FAMILY_W)
+    for (int l = 0; l < g.n_blocks; ++l) {
+      snprintf(nb, sizeof nb, "blk%d", l);
+      if ((st = w_cross_kv(c, R, nb, l)) != DIT_OK) return st;
+    }
 
   const int soff_img = P.has_txt_stream ? Nt : 0;
   float* x_img = x + (size_t)soff_img * d;
@@ -924,7 +944,7 @@ dit_status run_sample(dit_ctx* c, int n_req, const dit_req* reqs, float* latents
       off = 6 * d;
       for (int l = 0; l < g.n_blocks; ++l) {
         snprintf(nb, sizeof nb, "blk%d", l);
-        if ((st = w_block(c, R, nb, mstep)) != DIT_OK) return st;
+        if ((st = w_block(c, R, nb, mstep, l)) != DIT_OK) return st;
       }
     }
     // ---- final layer + latent update -----------------------------------------------------
