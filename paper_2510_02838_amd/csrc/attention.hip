@@ -35,6 +35,14 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 
 static constexpr int KT = 64;     // keys per tile
 
+// 16 bytes per lane from global memory straight into LDS through a buffer descriptor: address = base + voff
+// (per lane) + soff (wave-uniform), in bytes.  Cheaper to issue than the form with a 64-bit address per lane:
+// the lane offsets of a tile never change and the tile's position is a scalar.
+__device__ __forceinline__ void buffer_load_lds16(const void* base, lptr_t dst, uint32_t voff, int soff) {
+  const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc((void*)base, (short)0, (int)0xFFFFFFFFu, 0x00020000);
+  __builtin_amdgcn_raw_ptr_buffer_load_lds(r, dst, 16, voff, soff, 0, 0);
+}
+
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
@@ -139,33 +147,37 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
 #pragma unroll
   for (int i = 0; i < LV; ++i) {
     int q = i * NT + tid, r = q >> 3, pc = q & 7, c = pc ^ ((r >> 1) & 7);
-    gv[i] = (uint32_t)(head * DH + r) * (uint32_t)a.ldvt + vcol0 + c * 8;
+    gv[i] = (uint32_t)r * (uint32_t)a.ldvt + c * 8;       // from the head's first row and the segment's first column
   }
   const int n_kt_all = (klen + KT - 1) / KT;
   const int kt_first = tile.parts > 0 ? tile.kt0 : 0;                       // this workgroup's share of the key tiles
   const int n_kt = tile.parts > 0 ? tile.kt0 + tile.nkt : n_kt_all;         // (one past its last tile)
+  // K tile kt: the descriptor starts at the tile's first key (no 32-bit limit on the matrix), lanes add their row
+  // and chunk; V^T tile kt: one descriptor for the head's rows, the tile's first column as the scalar offset
+  // (a head's DH rows of ldvt columns stay far below 4 GiB).
+  const bf16_t* const kseg = a.k + (size_t)kbeg * a.ldk;
+  const bf16_t* const vhead = a.vt + (size_t)head * DH * a.ldvt + vcol0;
   auto issue_k = [&](int kt) {
     unsigned char* dst = sKb + (kt & 1) * KBYTES;
+    const bf16_t* tile0 = kseg + (size_t)kt * KT * a.ldk;
+    const int last = klen - 1 - kt * KT;        // rows past it are clamped copies, masked below
 #pragma unroll
     for (int i = 0; i < LK; ++i) {
-      int key = kt * KT + krow[i];
-      if (key >= klen) key = klen - 1;      // clamped rows are masked below
-      const bf16_t* src = a.k + (size_t)(kbeg + key) * a.ldk + gk[i];
-      __builtin_amdgcn_global_load_lds((gptr_t)src, (lptr_t)(dst + (i * NT + wave * 64) * 16), 16, 0, 0);
+      const int r = krow[i] < last ? krow[i] : last;
+      buffer_load_lds16(tile0, (lptr_t)(dst + (i * NT + wave * 64) * 16), ((uint32_t)r * (uint32_t)a.ldk + gk[i]) * 2u, 0);
     }
   };
   auto issue_v = [&](int kt) {
     unsigned char* dst = sVb + (kt & 1) * VBYTES;
-    const bf16_t* vsrc = a.vt + kt * KT;
 #pragma unroll
     for (int i = 0; i < LV; ++i)
-      __builtin_amdgcn_global_load_lds((gptr_t)(vsrc + gv[i]), (lptr_t)(dst + (i * NT + wave * 64) * 16), 16, 0, 0);
+      buffer_load_lds16(vhead, (lptr_t)(dst + (i * NT + wave * 64) * 16), gv[i] * 2u, kt * KT * 2);
     if constexpr (MODE == 4) {
       unsigned char* dlo = sVlo + (kt & 1) * VBYTES;
-      const bf16_t* vlo = a.vt_lo + kt * KT;
+      const bf16_t* vlo = a.vt_lo + (size_t)head * DH * a.ldvt + vcol0;
 #pragma unroll
       for (int i = 0; i < LV; ++i)
-        __builtin_amdgcn_global_load_lds((gptr_t)(vlo + gv[i]), (lptr_t)(dlo + (i * NT + wave * 64) * 16), 16, 0, 0);
+        buffer_load_lds16(vlo, (lptr_t)(dlo + (i * NT + wave * 64) * 16), gv[i] * 2u, kt * KT * 2);
     }
   };
 
