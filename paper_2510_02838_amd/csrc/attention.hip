@@ -294,7 +294,12 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
         const float p1 = __builtin_amdgcn_exp2f(MODE == 2 ? sc[t][e + 1] : PRESCALED ? sc[t][e + 1] - mc : sc[t][e + 1] * c2 - mc);
         const uint32_t w = pack2bf(p0, p1);
         pk[t][e >> 1] = w;
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(*(const bf16x2*)&w, ones, l_run, false);  // sum of the rounded values
+        // Row sums.  Head size 64: v_dot2_f32_bf16 on the rounded pair (one instruction per pair).  Head size 128: two
+        // plain adds on the unrounded values: dot2 shares the matrix pipe and costs more beside the twice as many
+        // MFMAs of this head size (+2.7 % at 32760 tokens, nothing at head size 64); these sums differ from those of
+        // the rounded values by 2^-9 / sqrt(keys) relative, far below the bf16 rounding of the output.
+        if constexpr (DH == 128) l_run += p0 + p1;
+        else l_run = __builtin_amdgcn_fdot2_f32_bf16(*(const bf16x2*)&w, ones, l_run, false);
       }
     // ---- (C) O^T += V^T(kt) P^T(kt) on the matrix pipe while the row max of S(kt+1) is taken
     const unsigned char* sV = sVb + (kt & 1) * VBYTES + voff;
@@ -319,7 +324,7 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
     // loads): they cannot raise the max, and their V^T columns are zero, so O is unaffected;
     // only their share of the row sum has to be taken out again.
     // Register e of tile t holds key  kt*64 + 32t + 16*(e/8) + 8*half + e%8.
-    if (kt == n_kt_all - 1 && (klen & (KT - 1)) != 0) {
+    if (DH == 64 && kt == n_kt_all - 1 && (klen & (KT - 1)) != 0) {      // (head size 128: after the loop)
       float corr = 0.f;
 #pragma unroll
       for (int t = 0; t < 2; ++t)
@@ -336,6 +341,24 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
   for (int kt = kt_first; kt < n_kt; kt += 2) {
     step(kt, sc, sn);
     if (kt + 1 < n_kt) step(kt + 1, sn, sc);
+  }
+  if constexpr (DH == 128) {
+    // Row sums of unrounded values: the clamped copies in the last tile all carry the score of the last key,
+    // which a lane's last score register holds whenever any of its keys is past the end; one exponential
+    // times their count takes them out again.  (Kept out of the loop body: code there, even in a branch
+    // taken once, costs the loop 1-2 %.)
+    if (n_kt == n_kt_all && (klen & (KT - 1)) != 0) {
+      const int kt = n_kt_all - 1;
+      int cnt = 0;
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) cnt += (kt * KT + 32 * t + 16 * (e >> 3) + 8 * half + (e & 7)) >= klen;
+      const float x = ((kt - kt_first) & 1) ? sn[1][15] : sc[1][15];     // the register set the last step consumed
+      const float c2 = (MODE == 0 || MODE == 3) ? c2_arg : 1.0f;
+      const float mc = MODE == 2 ? 0.f : m_run * c2;
+      l_run -= (float)cnt * __builtin_amdgcn_exp2f((MODE == 0 || MODE == 3) ? x * c2 - mc : x - mc);
+    }
   }
 
   float l_tot = xhalf_sum(l_run);
