@@ -320,47 +320,34 @@ __global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const At
       }
     }
     if constexpr (MODE != 2) mx = row_max(sn);
-    // Keys past the end of the segment in the last tile are copies of the last key (clamped
-    // loads): they cannot raise the max, and their V^T columns are zero, so O is unaffected;
-    // only their share of the row sum has to be taken out again.
-    // Register e of tile t holds key  kt*64 + 32t + 16*(e/8) + 8*half + e%8.
-    if (DH == 64 && kt == n_kt_all - 1 && (klen & (KT - 1)) != 0) {      // (head size 128: after the loop)
-      float corr = 0.f;
-#pragma unroll
-      for (int t = 0; t < 2; ++t)
-#pragma unroll
-        for (int e = 0; e < 16; e += 2) {
-          const int key = kt * KT + 32 * t + 16 * (e >> 3) + 8 * half + (e & 7);
-          const uint32_t msk = (key >= klen ? 0x3F80u : 0u) | (key + 1 >= klen ? 0x3F800000u : 0u);
-          const uint32_t w = pk[t][e >> 1];
-          corr = __builtin_amdgcn_fdot2_f32_bf16(*(const bf16x2*)&w, *(const bf16x2*)&msk, corr, false);
-        }
-      l_run -= corr;
-    }
   };
   for (int kt = kt_first; kt < n_kt; kt += 2) {
     step(kt, sc, sn);
     if (kt + 1 < n_kt) step(kt + 1, sn, sc);
   }
-  if constexpr (DH == 128) {
-    // Row sums of unrounded values: the clamped copies in the last tile all carry the score of the last key,
-    // which a lane's last score register holds whenever any of its keys is past the end; one exponential
-    // times their count takes them out again.  (Kept out of the loop body: code there, even in a branch
-    // taken once, costs the loop 1-2 %.)
-    if (n_kt == n_kt_all && (klen & (KT - 1)) != 0) {
-      const int kt = n_kt_all - 1;
-      int cnt = 0;
+  // Keys past the end of the segment in the last tile are copies of the last key (clamped loads): they cannot
+  // raise the max and their V^T columns are zero, so O is unaffected; only their share of the row sum has to be
+  // taken out again: the same exponentials once more (rounded to bf16 where the sums are those of the rounded
+  // values).  Register e of tile t holds key  kt*64 + 32t + 16*(e/8) + 8*half + e%8.
+  // (Kept out of the loop body: code there, even in a branch taken once, costs the loop 1-2 %.)
+  if (n_kt == n_kt_all && (klen & (KT - 1)) != 0) {
+    const int kt = n_kt_all - 1;
+    const bool in_sn = ((kt - kt_first) & 1) != 0;                     // the register set the last step consumed
+    const float c2 = (MODE == 0 || MODE == 3) ? c2_arg : 1.0f;
+    const float mc = MODE == 2 ? 0.f : m_run * c2;
+    float corr = 0.f;
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+    for (int t = 0; t < 2; ++t)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) cnt += (kt * KT + 32 * t + 16 * (e >> 3) + 8 * half + (e & 7)) >= klen;
-      const float x = ((kt - kt_first) & 1) ? sn[1][15] : sc[1][15];     // the register set the last step consumed
-      const float c2 = (MODE == 0 || MODE == 3) ? c2_arg : 1.0f;
-      const float mc = MODE == 2 ? 0.f : m_run * c2;
-      l_run -= (float)cnt * __builtin_amdgcn_exp2f((MODE == 0 || MODE == 3) ? x * c2 - mc : x - mc);
-    }
+      for (int e = 0; e < 16; ++e) {
+        const int key = kt * KT + 32 * t + 16 * (e >> 3) + 8 * half + (e & 7);
+        const float x = in_sn ? sn[t][e] : sc[t][e];
+        float pl = __builtin_amdgcn_exp2f((MODE == 0 || MODE == 3) ? x * c2 - mc : x - mc);
+        if constexpr (DH == 64) pl = __uint_as_float(pack2bf(pl, 0.f) << 16);
+        corr += key >= klen ? pl : 0.f;
+      }
+    l_run -= corr;
   }
-
   float l_tot = xhalf_sum(l_run);
   // ---- key-split block: leave the unnormalised sums; the last share to arrive adds them up ----
   if constexpr (MODE == 2) {
