@@ -39,23 +39,8 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
   const int lane = threadIdx.x & 63;
   const int nv = d >> 8;                       // float4 vectors per lane
   const float4* xr = (const float4*)(x + (size_t)row * d);
-  float4 v[MAXV];
-  float s = 0.f;
-#pragma unroll
-  for (int i = 0; i < MAXV; ++i)
-    if (i < nv) {
-      v[i] = xr[i * 64 + lane];
-      s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
-    }
-  const float mean = wave_sum(s) / (float)d;
-  float q = 0.f;
-#pragma unroll
-  for (int i = 0; i < MAXV; ++i)
-    if (i < nv) {
-      v[i].x -= mean; v[i].y -= mean; v[i].z -= mean; v[i].w -= mean;
-      q += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
-    }
-  const float rstd = rsqrtf(wave_sum(q) / (float)d + 1e-6f);
+  // The modulation vectors do not depend on the row's statistics: their loads go out with the row's own, ahead
+  // of the two reductions, instead of behind them.
   const float4 *sh, *sc;
   bool plus_one;
   if (gain) {
@@ -66,11 +51,35 @@ __global__ __launch_bounds__(256) void ln_modulate_kernel(const float* __restric
     sc = (const float4*)((second ? scale2 : scale) + mo); sh = (const float4*)((second ? shift2 : shift) + mo);
     plus_one = true;
   }
+  constexpr bool PRE = MAXV <= 12;        // (wider rows have no registers for it: there the loads stay behind)
+  float4 v[MAXV], ma[PRE ? MAXV : 1], mb[PRE ? MAXV : 1];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i)
+    if (i < nv) v[i] = xr[i * 64 + lane];
+  if constexpr (PRE) {
+#pragma unroll
+    for (int i = 0; i < MAXV; ++i)
+      if (i < nv) { ma[i] = sc[i * 64 + lane]; mb[i] = sh[i * 64 + lane]; }
+  }
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i)
+    if (i < nv) s += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+  const float mean = wave_sum(s) / (float)d;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i)
+    if (i < nv) {
+      v[i].x -= mean; v[i].y -= mean; v[i].z -= mean; v[i].w -= mean;
+      q += (v[i].x * v[i].x + v[i].y * v[i].y) + (v[i].z * v[i].z + v[i].w * v[i].w);
+    }
+  const float rstd = rsqrtf(wave_sum(q) / (float)d + 1e-6f);
   uint2* yr = (uint2*)(y + (size_t)row * d);
 #pragma unroll
   for (int i = 0; i < MAXV; ++i)
     if (i < nv) {
-      float4 a = sc[i * 64 + lane], b = sh[i * 64 + lane];
+      float4 a, b;
+      if constexpr (PRE) { a = ma[i]; b = mb[i]; } else { a = sc[i * 64 + lane]; b = sh[i * 64 + lane]; }
       if (plus_one) { a.x += 1.f; a.y += 1.f; a.z += 1.f; a.w += 1.f; }
       const float r0 = v[i].x * rstd * a.x + b.x, r1 = v[i].y * rstd * a.y + b.y;
       const float r2 = v[i].z * rstd * a.z + b.z, r3 = v[i].w * rstd * a.w + b.w;
@@ -94,6 +103,7 @@ void launch_ln_modulate(hipStream_t s, const float* x, bf16_t* y, int M, int d, 
   if (M == 0) return;
   dim3 g((M + 3) / 4), b(256);
   if (d <= 1024) hipLaunchKernelGGL(ln_modulate_kernel<4>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo, split, shift2, scale2);
+  else if (d <= 1536) hipLaunchKernelGGL(ln_modulate_kernel<6>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo, split, shift2, scale2);
   else if (d <= 3072) hipLaunchKernelGGL(ln_modulate_kernel<12>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo, split, shift2, scale2);
   else hipLaunchKernelGGL(ln_modulate_kernel<20>, g, b, 0, s, x, y, M, d, shift, scale, mod_stride, row_req, gain, beta, y_lo, split, shift2, scale2);
 }
