@@ -90,7 +90,10 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 // mantissa bits in the scores) and the values as two bf16 terms, V = vt + vt_lo, both multiplied by
 // the same probabilities: the rounding of k and v no longer shows in the output.
 template <int DH, int NW, int MODE>
-__global__ __launch_bounds__(NW * 64, NW == 4 ? 2 : 1) void attn_kernel(const AttnArgs a) {
+// Workgroups per CU: 4 waves at head size 64 fit 168 registers, so three workgroups share a CU (three waves per
+// SIMD overlap their exponentials and matrix instructions better than two: +8 % at 4250 tokens); head size 128
+// needs ~230 registers: two workgroups of 4 waves, or one of 8.
+__global__ __launch_bounds__(NW * 64, NW == 4 ? (DH == 64 ? 3 : 2) : 1) void attn_kernel(const AttnArgs a) {
   constexpr int NT = NW * 64;
   constexpr int KROW = DH * 2;                 // bytes per K-tile row
   constexpr int KCPR = DH / 8;                 // 16-byte chunks per K-tile row

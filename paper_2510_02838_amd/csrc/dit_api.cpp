@@ -252,10 +252,11 @@ size_t put(std::vector<unsigned char>& m, const std::vector<T>& v) {
 }
 
 // Key-split of the attention blocks in the last, partly filled round.  The chip's 8 XCDs take the workgroups
-// of a launch in turn, each running its share in rounds of (32 CUs x workgroups per CU); when every block
-// costs the same (requests of one shape) a launch of 1.6 rounds takes as long as one of 2.  The blocks of the
-// partial round are cut into 2-4 shares of their key tiles, so that this round is made of shorter workgroups
-// that fill all CUs: 102 blocks per XCD on 64 slots become 63 whole blocks and 39 x 3 shares, 1 + 2/3 rounds.
+// of a launch in turn, each running its share in rounds of (32 CUs x workgroups per CU: 3 of 128 queries at
+// head size 64, 2 at head size 128, 1 of 256 queries); when every block costs the same (requests of one
+// shape) a launch of 1.1 rounds takes as long as one of 2.  The blocks of the partial round are cut into 2-4
+// shares of their key tiles, so that this round is made of shorter workgroups that fill all CUs: 102 blocks
+// per XCD on 96 slots become 96 whole blocks and 6 x 4 shares, 1 + 1/4 rounds.
 // Needs a head count that is a multiple of 8 (each XCD owns whole heads: all shares of a block meet in one L2).
 void plan_attention_split(Plan& P, const dit_config& g) {
   P.tiles_split.clear(); P.split_slots = 0; P.split_parts = 1;
@@ -265,7 +266,7 @@ void plan_attention_split(Plan& P, const dit_config& g) {
   for (const AttnTile& t : P.tiles)
     if (P.cu_joint[t.seg + 1] - P.cu_joint[t.seg] != klen) return;       // mixed lengths: longest-first order handles the tail
   const int hpx = g.n_heads / 8, n_kt = (klen + 63) / 64;
-  const int slots = 32 * (P.qb == 128 ? 2 : 1);                            // workgroups one XCD holds at a time
+  const int slots = 32 * (P.qb == 128 ? (g.head_dim == 64 ? 3 : 2) : 1);   // workgroups one XCD holds at a time
   const int per_xcd = (int)P.tiles.size() * hpx;
   const int rem = per_xcd % slots;
   if (per_xcd <= slots || rem == 0) return;

@@ -715,11 +715,11 @@ def test_sd3_width_low_resolution_requests_split_k_path(torch):
             assert not np.array_equal(fg[0], fg[1])
 
 
-@pytest.mark.parametrize("reqs", [[(1, 104, 104, 112)], [(1, 62, 64, 154)] * 3])
+@pytest.mark.parametrize("reqs", [[(1, 96, 192, 154)], [(1, 62, 64, 154)] * 4])
 def test_attention_key_split_two_and_four_shares(torch, reqs):
     """SD3 width, 1 block, token counts whose query blocks leave a nearly empty last round of the chip
-    (22 blocks of 128 queries x 3 heads per XCD on 64 workgroup slots: 4 shares; a same-shape batch of
-    three with 27 blocks and 18 key tiles per block: 2 shares).  A step against the oracle, and twice
+    (38 blocks of 128 queries x 3 heads per XCD on 96 workgroup slots: 4 shares; a same-shape batch of
+    four with 36 blocks and 18 key tiles per block: 2 shares).  A step against the oracle, and twice
     for bit-equality (the shares are added in a fixed order whichever finishes last)."""
     arch = dict(synth.CONFIGS["sd3"]["arch"], n_blocks=1)
     case = Case(torch, arch, reqs, 2, shifts=[1.0] * len(reqs))

@@ -71,19 +71,19 @@ def test_workspace_size_grows_with_batch_and_steps(B):
 
 
 def test_attention_plan_splits_the_last_round_of_same_shape_blocks(B):
-    """Host arithmetic of the self-attention launch.  An XCD (32 CUs, 2 workgroups of 128 queries each per CU)
-    holds 64 workgroups at a time and owns n_heads/8 heads; blocks that would make a partly filled last round
-    are cut into key-split shares when that saves at least a quarter of a round."""
+    """Host arithmetic of the self-attention launch.  An XCD (32 CUs; 3 workgroups of 128 queries per CU at head
+    size 64, 2 at head size 128, 1 of 256 queries) holds 96 / 64 / 32 workgroups at a time and owns n_heads/8
+    heads; blocks that would make a partly filled last round are cut into key-split shares when that saves at
+    least a quarter of a round."""
     sd3 = B.DiT(synth.CONFIGS["sd3"]["arch"], bind=False)
-    # 4250 tokens: 34 blocks x 3 heads = 102 per XCD = 64 + 38: the last 13 blocks of every head in 3 shares
-    assert sd3.attention_plan(synth.make_requests("sd3")) == (128, 34, 13, 3)
-    assert sd3.attention_plan([(1, 104, 104, 112)]) == (128, 22, 1, 4)     # 66 per XCD: 2 over a round
-    assert sd3.attention_plan([(1, 96, 118, 112)]) == (128, 23, 2, 4)      # 69 per XCD: 5 over
-    assert sd3.attention_plan([(1, 128, 128, 154)] * 2) == (128, 68, 4, 4) # same-shape batch: 204 = 3 x 64 + 12
-    # 3 x 1146 tokens: 27 blocks per head, 81 per XCD; 18 key tiles per block allow two shares only (8 tiles each at least)
-    assert sd3.attention_plan([(1, 62, 64, 154)] * 3) == (128, 27, 6, 2)
+    # 4250 tokens: 34 blocks x 3 heads = 102 per XCD = 96 + 6: the last 2 blocks of every head in 4 shares
+    assert sd3.attention_plan(synth.make_requests("sd3")) == (128, 34, 2, 4)
+    assert sd3.attention_plan([(1, 96, 192, 154)]) == (128, 38, 6, 4)      # 114 per XCD: 18 over a round
+    assert sd3.attention_plan([(1, 128, 128, 154)] * 2) == (128, 68, 4, 4) # same-shape batch: 204 = 2 x 96 + 12
+    # 4 x 1146 tokens: 36 blocks per head, 108 per XCD; 18 key tiles per block allow two shares only (8 tiles each at least)
+    assert sd3.attention_plan([(1, 62, 64, 154)] * 4) == (128, 36, 4, 2)
     assert sd3.attention_plan([(1, 32, 32, 154)])[2:] == (0, 1)            # 4 blocks: one round, nothing to split
-    assert sd3.attention_plan([(1, 96, 192, 154)])[2:] == (0, 1)           # 114 per XCD: 50 over, no share count pays
+    assert sd3.attention_plan([(1, 104, 104, 112)])[2:] == (0, 1)          # 66 per XCD: one round
     assert sd3.attention_plan(synth.make_requests("hetero8"))[2:] == (0, 1)   # mixed shapes: longest-first order instead
     sd3.close()
     flux = B.DiT(synth.CONFIGS["flux"]["arch"], bind=False)
