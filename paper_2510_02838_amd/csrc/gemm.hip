@@ -888,6 +888,15 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
       t256 += (long long)((b.p[i].M + 255) / 256) * ((b.p[i].N + 255) / 256);
     const long long rem = t256 % 256;
     tile = (t256 >= 1024 || (t256 >= 256 && (rem == 0 || rem >= 64))) ? 1256256 : 128128;
+    // Below one round of 256x256 tiles: a round of them does the work of two rounds of 128x128 pairs in about
+    // 1.67 times the time of one, so the big tile wins whenever the small one needs two rounds or more of its
+    // 512 slots (216 tiles of 256x256 against 864 of 128x128 at 4608 x 3072 x 15360: 350 against 410 us).
+    if (tile == 128128 && t256 < 256) {
+      long long t128 = 0;
+      for (int i = 0; i < b.n; ++i)
+        t128 += (long long)((b.p[i].M + 127) / 128) * ((b.p[i].N + 127) / 128);
+      if (100 * ((t128 + 511) / 512) > 167) tile = 1256256;      // (t256 < 256: one round of the big tile)
+    }
     // A 320-row tile when it saves rounds: the 4250-row QKV product of the 1024^2 request is 306 tiles of
     // 256x256 (a second round for 50 tiles) but 252 of 320x256, one round of tiles 1.25 times as long (measured
     // 56 us against 71 us with 128x128 tiles and 77 us with 256x256); 864 tiles (4 rounds) against 720 (3 rounds
