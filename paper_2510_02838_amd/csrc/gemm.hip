@@ -74,7 +74,6 @@ __device__ __forceinline__ float gelu_tanh(float x) {
 template <int BKT>
 __device__ __forceinline__ int swz_key(int r) { return BKT == 64 ? ((r >> 1) & 7) : ((r >> 2) & 3); }
 
-typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
 
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
@@ -140,15 +139,16 @@ __device__ __forceinline__ void tile_coords(const GemmProblem& P, int t, int& tm
 // tile's k-loop runs at global-memory latency per slab).
 // CONV: every problem of the batch is a 3x3 convolution (GemmProblem::conv_w > 0); a separate
 // instantiation so that the plain product's address arithmetic stays as it is.
-// SCHED: how slabs are fetched and how the loop is laid out.
-//   0  global_load_lds with 64-bit lane addresses (kept for the convolution addressing, whose image
-//      stacks may exceed the 4 GiB a 32-bit byte offset reaches)
-//   2  buffer_load ... lds: descriptor in SGPRs, one 32-bit byte offset per lane that never changes, the k
-//      advance in an SGPR: no vector address arithmetic in the loop and a cheaper issue (measured +2..7 %)
-//   3  as 2 with the loop rotated: an iteration starts right after the barrier with the LAST k-step of a
+// Slabs are fetched with buffer_load ... lds: descriptor in SGPRs, one 32-bit byte offset per lane, taken
+// from the tile's first row (for a convolution: from that row's window) and never changing, the k advance
+// in an SGPR: no vector address arithmetic in the loop and a cheaper issue than global_load_lds with
+// 64-bit lane addresses (measured +2..7 %, convolutions +2.5 %).
+// SCHED: how the loop is laid out.
+//   2  k-steps of a slab in order, the barrier after the last fragment read
+//   3  the loop rotated: an iteration starts right after the barrier with the LAST k-step of a
 //      slab, so its first MFMAs wait for no LDS read (measured 0..+3 % on the 8-wave 256x256 tile, not on
 //      the 4-wave 128x128 one)
-template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE, bool CONV = false, int SCHED = 0>
+template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE, bool CONV = false, int SCHED = 2>
 __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batch) {
   constexpr int NT = WM * WN * 64;
   constexpr int TM = BM / WM / 32, TN = BN / WN / 32;
@@ -185,6 +185,13 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
   // ---- per-thread global source offsets ------------------------------------------------
   // (element offsets from the matrix base; every operand is far below 2^31 elements)
   uint32_t ga[LA], gb[LB];
+  size_t conv_pix0 = 0;        // convolution: window of row m0 in the stack of bordered images
+  if constexpr (CONV) {
+    const int mm = m0 < P.M ? m0 : P.M - 1;
+    const int b = mm / P.conv_img, r = mm - b * P.conv_img;
+    const int y = r / P.conv_w, x = r - y * P.conv_w;
+    conv_pix0 = (size_t)(b * (P.conv_img / P.conv_w + 2) + y) * (P.conv_w + 2) + x;
+  }
 #pragma unroll
   for (int i = 0; i < LA; ++i) {
     int q = i * NT + tid, r = q / CPR, pc = q % CPR, c = pc ^ swz_key<BKT>(r);
@@ -192,17 +199,17 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     if constexpr (CONV) {    // top-left pixel of the 3x3 window in the stack of bordered images
       const int b = m / P.conv_img, r = m - b * P.conv_img;
       const int y = r / P.conv_w, x = r - y * P.conv_w;
-      ga[i] = (uint32_t)((b * (P.conv_img / P.conv_w + 2) + y) * (P.conv_w + 2) + x) * (uint32_t)P.conv_cin + c * 8;
-    } else if constexpr (SCHED >= 2) {
-      ga[i] = (uint32_t)(m - m0) * (uint32_t)P.lda + c * 8;    // from the tile's first row (the buffer form's base)
+      const size_t pix = (size_t)(b * (P.conv_img / P.conv_w + 2) + y) * (P.conv_w + 2) + x;
+      // from the window of the tile's first row (pixels of later rows lie behind it)
+      ga[i] = (uint32_t)((pix - conv_pix0) * (size_t)P.conv_cin) + c * 8;
     } else {
-      ga[i] = (uint32_t)m * (uint32_t)P.lda + c * 8;
+      ga[i] = (uint32_t)(m - m0) * (uint32_t)P.lda + c * 8;    // from the tile's first row (the buffer's base)
     }
   }
 #pragma unroll
   for (int i = 0; i < LB; ++i) {
     int q = i * NT + tid, r = q / CPR, pc = q % CPR, c = pc ^ swz_key<BKT>(r);
-    gb[i] = (uint32_t)((SCHED >= 2 ? 0 : n0) + r) * (uint32_t)P.ldw + c * 8; // weights are padded to N_pad rows
+    gb[i] = (uint32_t)r * (uint32_t)P.ldw + c * 8; // weights are padded to N_pad rows
   }
 
 
@@ -220,9 +227,9 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     P.A += kb * BKT; P.W += kb * BKT;
     nk = ke - kb;
   }
-  // buffer form: lanes address their tile by 32-bit byte offsets from its first row, so no operand size limit
-  const bf16_t* const tileA = (SCHED >= 2 && !CONV) ? P.A + (size_t)m0 * P.lda : P.A;
-  const bf16_t* const tileW = SCHED >= 2 ? P.W + (size_t)n0 * P.ldw : P.W;
+  // lanes address their tile by 32-bit byte offsets from its first row, so no operand size limit
+  const bf16_t* const tileA = CONV ? P.A + conv_pix0 * (size_t)P.conv_cin : P.A + (size_t)m0 * P.lda;
+  const bf16_t* const tileW = P.W + (size_t)n0 * P.ldw;
   const int half = lane >> 5;
   // LDS byte offsets of this lane's fragment rows (the chunk index is XORed in per k-step;
   // the key is the same for rows 32 apart)
@@ -243,21 +250,10 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
       ka = (ky * (P.conv_w + 2) + kx) * P.conv_cin + c0;
     }
     unsigned char* dB = dA + OFFB;
-    if constexpr (SCHED >= 2) {      // buffer form: fixed 32-bit lane offsets, the k advance in an SGPR
 #pragma unroll
-      for (int i = 0; i < LA; ++i) buffer_load_lds16(tileA, (lptr_t)(dA + (i * NT + wave * 64) * 16), ga[i] * 2u, ka * 2);
+    for (int i = 0; i < LA; ++i) buffer_load_lds16(tileA, (lptr_t)(dA + (i * NT + wave * 64) * 16), ga[i] * 2u, ka * 2);
 #pragma unroll
-      for (int i = 0; i < LB; ++i) buffer_load_lds16(tileW, (lptr_t)(dB + (i * NT + wave * 64) * 16), gb[i] * 2u, ks * 2);
-    } else {
-      const bf16_t* Ak = P.A + ka;
-      const bf16_t* Wk = P.W + ks;
-#pragma unroll
-      for (int i = 0; i < LA; ++i)
-        __builtin_amdgcn_global_load_lds((gptr_t)(Ak + ga[i]), (lptr_t)(dA + (i * NT + wave * 64) * 16), 16, 0, 0);
-#pragma unroll
-      for (int i = 0; i < LB; ++i)
-        __builtin_amdgcn_global_load_lds((gptr_t)(Wk + gb[i]), (lptr_t)(dB + (i * NT + wave * 64) * 16), 16, 0, 0);
-    }
+    for (int i = 0; i < LB; ++i) buffer_load_lds16(tileW, (lptr_t)(dB + (i * NT + wave * 64) * 16), gb[i] * 2u, ks * 2);
   };
   auto load_frags = [&](const unsigned char* st, int kk, bf16x8 (&a)[TM], bf16x8 (&b)[TN]) {
     const int c = kk * 2 + half;
@@ -280,7 +276,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
 #pragma unroll
   for (int sidx = 0; sidx < NS; ++sidx) issue(sidx);
   wait_vm<(NS - 1) * LPS, false>();          // slab 0 has landed (mine)
-  if constexpr (SCHED >= 2) wg_barrier(); else __syncthreads();   // ... and everyone's
+  wg_barrier();   // ... and everyone's
   load_frags(smem, 0, a0, b0);
   if constexpr (SCHED == 3) {
     // Rotated loop: an iteration starts right after the barrier (nothing outstanding on LDS, so its first
@@ -336,7 +332,7 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     // flight.  Wait for slab kt+1 (mine) and my fragments; after the barrier nobody reads `cur`
     // any more and `nxt` is visible to all.
     wait_vm<(NS - 2) * LPS, true>();
-    if constexpr (SCHED >= 2) wg_barrier(); else __syncthreads();
+    wg_barrier();
     issue(kt + NS);                          // into the stage of slab kt
     load_frags(nxt, 0, a0, b0);              // (after the last slab this reads a stale stage; unused)
     mfma_all(a1, b1);
@@ -776,7 +772,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const GemmBatch batc
   }
 }
 
-template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE = 0, bool CONV = false, int SCHED = 0>
+template <int BM, int BN, int WM, int WN, int BKT, int NS, int MODE = 0, bool CONV = false, int SCHED = 2>
 static void launch_t(hipStream_t s, GemmBatch& b) {
   int total = 0;
   for (int i = 0; i < b.n; ++i) {
@@ -928,9 +924,9 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
     if (plain) return -1;
     for (int i = 0; i < b.n; ++i)        // whole images of whole rows
       if (b.p[i].conv_img <= 0 || b.p[i].conv_img % b.p[i].conv_w || b.p[i].M % b.p[i].conv_img) return -1;
-    if (tile == 1256256) launch_t<256, 256, 2, 4, 64, 2, 0, true>(s, b);
-    else if (tile == 30128128) launch_t<128, 128, 2, 2, 64, 4, 0, true>(s, b);
-    else { tile = 128128; launch_t<128, 128, 2, 2, 64, 2, 0, true>(s, b); }
+    if (tile == 1256256) launch_t<256, 256, 2, 4, 64, 2, 0, true, 3>(s, b);
+    else if (tile == 30128128) launch_t<128, 128, 2, 2, 64, 4, 0, true, 2>(s, b);
+    else { tile = 128128; launch_t<128, 128, 2, 2, 64, 2, 0, true, 2>(s, b); }
     return tile;
   }
   switch (tile) {
