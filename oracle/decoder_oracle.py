@@ -25,14 +25,15 @@ GN_GROUPS = 32
 GN_EPS = 1e-6
 
 
-def param_shapes(arch):
+def param_shapes(arch, kt=1):
     """{name: (shape, kind)}; conv weights are matrices [taps*C_in, C_out] with the input index
-    (ky*3 + kx)*C_in + c (1x1: just c)."""
+    (ky*3 + kx)*C_in + c (1x1: just c).  kt = 3: the 3x3 convolutions also span three frames
+    (the video decoder's), input index ((kf*3 + ky)*3 + kx)*C_in + c."""
     ch, zc, oc = arch["channels"], arch["latent_ch"], arch["out_ch"]
     out = {}
 
     def conv(name, cin, cout, k):
-        out[name + ".w"] = ((k * k * cin, cout), "matrix")
+        out[name + ".w"] = (((kt if k == 3 else 1) * k * k * cin, cout), "matrix")
         out[name + ".b"] = ((cout,), "bias")
 
     def gn(name, c):

@@ -113,3 +113,8 @@ DECODERS = {
     "ae_tiny": dict(latent_ch=16, out_ch=3, channels=(128, 128, 64, 64), n_res=2),
     "ae_kl": dict(latent_ch=16, out_ch=3, channels=(512, 512, 256, 128), n_res=3),
 }
+# causal video decoders (3x3x3 convolutions; t_up: level transitions that also double the frame rate)
+VIDEO_DECODERS = {
+    "vae3d_tiny": dict(latent_ch=16, out_ch=3, channels=(128, 64, 64), n_res=1, t_up=1),
+    "vae3d": dict(latent_ch=16, out_ch=3, channels=(512, 512, 256, 128), n_res=3, t_up=2),
+}
