@@ -68,7 +68,7 @@ void add_vec(dec_ctx* c, const std::string& name, int n, int kind) {
 }
 void add_conv(dec_ctx* c, const std::string& name, int cin, int cout, int k) {
   DTensor t;
-  t.name = name + ".w"; t.taps = k * k; t.cin = cin; t.cin_pad = (int)rup(cin, 64);
+  t.name = name + ".w"; t.taps = k * k * (k == 3 && c->cfg.temporal ? 3 : 1); t.cin = cin; t.cin_pad = (int)rup(cin, 64);
   t.rows_in = t.taps * cin; t.cols_out = cout; t.kind = 0; t.off = c->weight_bytes;
   t.ld = t.taps * t.cin_pad; t.rows_pad = (int)rup(cout, 256);
   c->weight_bytes += rup((size_t)t.rows_pad * t.ld * 2, 256);
@@ -110,6 +110,7 @@ uint16_t h_f2bf(float f) {
 struct Layout {
   size_t map, xa, xb, t, img, act, q, k, v, vt, sc, pm, gnp, gst, out4, partial, total;
   int Hf, Wf, P0, P0pad;          // final image size; latent pixels and their padding to 64
+  int n_out;                      // images at the output (a video's frame count grows with the frame rate)
 };
 constexpr size_t PARTIAL_BYTES = (size_t)256 * 128 * 128 * 4;
 
@@ -118,20 +119,32 @@ constexpr size_t PARTIAL_BYTES = (size_t)256 * 128 * 128 * 4;
 // stack of n bordered images of the widest level, below 2^32 elements (32-bit offsets in the
 // kernels); n images: 1..GN_MAX_BATCH, and with n > 1 h*w a multiple of 256 (group-norm chunks
 // must not straddle images)
+// frames (images) at the output of a video decoder that starts with n: 2F - 1 per frame-rate doubling
+long long frames_out(const dec_ctx* c, long long n) {
+  if (c->cfg.temporal)
+    for (int l = 0; l < c->cfg.t_up; ++l) n = 2 * n - 1;
+  return n;
+}
 bool size_ok(const dec_ctx* c, int n, int h, int w) {
   if (!(h >= 1 && w >= 1 && h <= 4096 && w <= 4096 && ((long long)h * w) % 64 == 0 && (long long)h * w <= 65536)) return false;
-  if (n < 1 || n > GN_MAX_BATCH || (n > 1 && ((long long)h * w) % 256 != 0)) return false;
+  const long long nf = n >= 1 ? frames_out(c, n) : 0;
+  if (n < 1 || nf > GN_MAX_BATCH || (nf > 1 && ((long long)h * w) % 256 != 0)) return false;
   const int up = 1 << (c->cfg.n_levels - 1);
   const long long Hf = (long long)h * up, Wf = (long long)w * up;
-  if (Hf > 65535 || n * Hf * Wf >= (1LL << 31) / 4) return false;
+  if (Hf > 65535 || nf * Hf * Wf >= (1LL << 31) / 4) return false;
   // the widest bordered stack of each level: its own width, and the previous level's after the upsampling
-  long long H = h, W = w, worst = 0;
+  // (a video's stacks start with two zero frames)
+  const long long pad = c->cfg.temporal ? 2 : 0;
+  long long H = h, W = w, worst = 0, F = n;
   int prev = std::max(c->cfg.channels[0], 64);
   for (int l = 0; l < c->cfg.n_levels; ++l) {
     const int ch = c->cfg.channels[l];
-    worst = std::max(worst, n * (H + 2) * (W + 2) * std::max(ch, prev));
+    worst = std::max(worst, (F + pad) * (H + 2) * (W + 2) * std::max(ch, prev));
     prev = ch;
-    if (l != c->cfg.n_levels - 1) { H *= 2; W *= 2; worst = std::max(worst, n * (H + 2) * (W + 2) * ch); }
+    if (l != c->cfg.n_levels - 1) {
+      if (c->cfg.temporal && l < c->cfg.t_up) F = 2 * F - 1;
+      H *= 2; W *= 2; worst = std::max(worst, (F + pad) * (H + 2) * (W + 2) * ch);
+    }
   }
   return worst < (1LL << 32);
 }
@@ -142,23 +155,28 @@ void plan(const dec_ctx* c, int n, int h, int w, Layout& L) {
   L.Hf = h * up; L.Wf = w * up;
   L.P0 = h * w; L.P0pad = (int)rup(L.P0, 256);        // rows of k as the product's second operand are read up to a multiple of 256
   // the largest stream / image / intermediate over the levels
+  // (n streams / bordered images back to back; a video's frame count grows on the way and its stacks of
+  // bordered images start with two zero frames)
   size_t max_x = 0, max_img = 0;
   int H = h, W = w;
   int prev = g.channels[0];
-  max_x = std::max(max_x, (size_t)H * W * prev);
-  max_img = std::max(max_img, (size_t)(H + 2) * (W + 2) * std::max(prev, 64));
+  size_t F = n;
+  const size_t pad = g.temporal ? 2 : 0;
+  max_x = std::max(max_x, F * H * W * prev);
+  max_img = std::max(max_img, (F + pad) * (H + 2) * (W + 2) * std::max(prev, 64));
   for (int l = 0; l < g.n_levels; ++l) {
     const int ch = g.channels[l];
-    max_x = std::max(max_x, (size_t)H * W * std::max(ch, prev));
-    max_img = std::max(max_img, (size_t)(H + 2) * (W + 2) * std::max(ch, prev));
+    max_x = std::max(max_x, F * H * W * std::max(ch, prev));
+    max_img = std::max(max_img, (F + pad) * (H + 2) * (W + 2) * std::max(ch, prev));
     prev = ch;
     if (l != g.n_levels - 1) {
+      if (g.temporal && l < g.t_up) F = 2 * F - 1;
       H *= 2; W *= 2;
-      max_img = std::max(max_img, (size_t)(H + 2) * (W + 2) * ch);
-      max_x = std::max(max_x, (size_t)H * W * ch);
+      max_img = std::max(max_img, (F + pad) * (H + 2) * (W + 2) * ch);
+      max_x = std::max(max_x, F * H * W * ch);
     }
   }
-  max_x *= n; max_img *= n;                                  // n streams / bordered images back to back
+  L.n_out = (int)F;
   const size_t C0 = g.channels[0];
   size_t o = 0;
   auto take = [&](size_t bytes) { const size_t at = o; o += rup(bytes, 256); return at; };
@@ -171,9 +189,9 @@ void plan(const dec_ctx* c, int n, int h, int w, Layout& L) {
   L.sc = take((size_t)L.P0 * L.P0 * 4);
   L.pm = take((size_t)L.P0 * rup(L.P0, 64) * 2);
   // channel sums per chunk of 64 pixels at least (the smallest wave height of a product tile)
-  L.gnp = take(std::max(group_norm_partial_bytes((long long)n * L.Hf * L.Wf, 1024), max_x / 64 * 8 + 2 * 1024 * 8));
+  L.gnp = take(std::max(group_norm_partial_bytes((long long)L.n_out * L.Hf * L.Wf, 1024), max_x / 64 * 8 + 2 * 1024 * 8));
   L.gst = take(GN_STATS_BYTES);
-  L.out4 = take((size_t)n * L.Hf * L.Wf * 4 * 4);
+  L.out4 = take((size_t)L.n_out * L.Hf * L.Wf * 4 * 4);
   L.partial = take(PARTIAL_BYTES);
   L.total = o;
 }
@@ -191,7 +209,8 @@ GemmProblem prob(const bf16_t* A, int lda, const bf16_t* W, int ldw, const float
 
 struct Fwd {
   dec_ctx* c; const Layout& L; unsigned char* ws; hipStream_t s;
-  int B;                                   // images in this call
+  mutable int B;                           // images (frames) at the current level
+  int kt = 1;                              // frame taps of the 3x3 convolutions: 1, or 3 for a video
   // the buffer whose per-chunk channel sums the last convolution left in the group-norm scratch
   mutable const float* stats_of = nullptr;
   mutable int stats_chunks = 0;
@@ -207,11 +226,12 @@ struct Fwd {
     return launch_gemm(s, b);
   }
   // 3x3 convolution of the bordered bf16 image `img` (H x W, cin_pad channels) into fp32 rows
+  // (a video's stack starts with two zero frames: `img` is the stack, frame() its first real image)
   void conv3(const std::string& name, const bf16_t* img, int H, int W, int kind, float* out, int ldc, bool sums = true) const {
     const DTensor* t = find(c, name + ".w");
     GemmProblem p = prob(img, t->cin_pad, Wm(c, name + ".w"), t->ld, Wv(c, name + ".b"), B * H * W, t->cols_out,
-                         9 * t->cin_pad, kind, out, ldc);
-    p.conv_w = W; p.conv_cin = t->cin_pad; p.conv_img = H * W;
+                         9 * kt * t->cin_pad, kind, out, ldc);
+    p.conv_w = W; p.conv_cin = t->cin_pad; p.conv_img = H * W; p.conv_kt = kt;
     const bool want = sums && (kind == OUT_F32 || kind == OUT_RESID_F32);   // a group norm reads `out` next
     if (want) p.stats = at<float>(L.gnp);
     const int tile = gemm({p});
@@ -226,15 +246,18 @@ struct Fwd {
     launch_group_norm(s, x, Wv(c, name + ".g"), Wv(c, name + ".b"), out, at<float>(L.gnp), at<float2>(L.gst), H, W, C,
                       GROUPS, silu, pad, x == stats_of ? stats_chunks : 0, B);
   }
+  // first real image of the stack of bordered images of H x W x C
+  bf16_t* frame(int H, int W, int C) const { return at<bf16_t>(L.img) + (kt == 3 ? (size_t)2 * (H + 2) * (W + 2) * C : 0); }
   void zero_img(int H, int W, int C) const {       // the border must be zero; the interior is overwritten
-    launch_zero_border(s, at<bf16_t>(L.img), H, W, C, B);
+    if (kt == 3) launch_fill_u16(s, at<bf16_t>(L.img), (long long)2 * (H + 2) * (W + 2) * C, 0);   // the two frames before the first
+    launch_zero_border(s, frame(H, W, C), H, W, C, B);
   }
   // x (cin channels, in `x`) -> result (cout channels) in `y`; y == x when cin == cout
   void res(const std::string& name, float* x, float* y, int H, int W, int cin, int cout) const {
     bf16_t* img = at<bf16_t>(L.img);
     float* t = at<float>(L.t);
     zero_img(H, W, cin);
-    gn(name + ".gn1", x, img, H, W, cin, 1, 1);
+    gn(name + ".gn1", x, frame(H, W, cin), H, W, cin, 1, 1);
     conv3(name + ".conv1", img, H, W, OUT_F32, t, cout);
     if (cin != cout) {
       launch_cast_bf16(s, x, at<bf16_t>(L.act), (long long)B * H * W * cin);
@@ -242,7 +265,7 @@ struct Fwd {
                  B * H * W, cout, cin, OUT_F32, y, cout)});
     }
     zero_img(H, W, cout);
-    gn(name + ".gn2", t, img, H, W, cout, 1, 1);
+    gn(name + ".gn2", t, frame(H, W, cout), H, W, cout, 1, 1);
     conv3(name + ".conv2", img, H, W, OUT_RESID_F32, y, cout);
   }
 };
@@ -278,6 +301,7 @@ dit_status dec_create(const dec_config* cfg, int device, void* hip_stream, dec_c
     if (ch != 64 && ch != 128 && ch != 256 && ch != 512 && ch != 1024) return DIT_ESHAPE;
   }
   if (g.channels[0] % 128) return DIT_ESHAPE;      // the mid-block attention transposes v in 128-channel slices
+  if ((g.temporal != 0 && g.temporal != 1) || g.t_up < 0 || g.t_up > g.n_levels - 1 || (!g.temporal && g.t_up)) return DIT_EINVAL;
   dec_ctx* c = new dec_ctx();
   c->cfg = g; c->device = device; c->stream = (hipStream_t)hip_stream;
   const int* ch = g.channels;
@@ -343,6 +367,8 @@ dit_status dec_init_weights(dec_ctx* c, uint64_t seed, float std) {
   DHIP(c, hipGetLastError());
   return DIT_OK;
 }
+
+int dec_frames_out(const dec_ctx* c, int n) { return c && n >= 1 ? (int)std::min<long long>(frames_out(c, n), 0x7FFFFFFF) : 0; }
 
 int dec_tensor_count(const dec_ctx* c) { return c ? (int)c->tensors.size() : 0; }
 dit_status dec_tensor_info(const dec_ctx* c, int i, char* name, size_t len, int* rows_in, int* cols_out, int* kind) {
@@ -412,8 +438,8 @@ dit_status dec_forward(dec_ctx* c, int n, int h, int w, const float* latent, flo
   if (!c->weights || !c->ws) return dfail(c, DIT_EINVAL, "dec_bind has not been called");
   if (!latent || !image) return dfail(c, DIT_EINVAL, "null latent or image");
   if (!size_ok(c, n, h, w))
-    return dfail(c, DIT_ESHAPE, "%d latent(s) of %d x %d: sides 1..4096, pixel count a multiple of 64 (256 for a batch) and at most 65536, "
-                 "1..%d images, their bordered stack below 2^32 elements per level", n, h, w, GN_MAX_BATCH);
+    return dfail(c, DIT_ESHAPE, "%d latent(s) of %d x %d: sides 1..4096, pixel count a multiple of 64 (256 for a batch or a video) and at most 65536, "
+                 "1..%d images or output frames, their bordered stack below 2^32 elements per level", n, h, w, GN_MAX_BATCH);
   const dec_config& g = c->cfg;
   DHIP(c, hipSetDevice(c->device));
   Layout L;
@@ -421,6 +447,8 @@ dit_status dec_forward(dec_ctx* c, int n, int h, int w, const float* latent, flo
   if (L.total > c->ws_bytes) return dfail(c, DIT_ENOMEM, "workspace has %zu bytes, this call needs %zu", c->ws_bytes, L.total);
   hipStream_t s = c->stream;
   Fwd F{c, L, c->ws, s, n};
+  F.kt = g.temporal ? 3 : 1;
+  const int pad_frames = g.temporal ? 2 : 0;
   // identity column map of the mid-block's value transpose
   if (c->map_done) DHIP(c, hipEventSynchronize(c->map_done));
   else DHIP(c, hipEventCreateWithFlags(&c->map_done, hipEventDisableTiming));
@@ -436,8 +464,8 @@ dit_status dec_forward(dec_ctx* c, int n, int h, int w, const float* latent, flo
   int H = h, W = w;
   // conv_in: latents (channels-first fp32) -> bordered bf16 images with the channels padded to 64
   const DTensor* tin = find(c, "conv_in.w");
-  launch_fill_u16(s, img, (long long)n * (H + 2) * (W + 2) * tin->cin_pad, 0);
-  launch_latent_to_image(s, latent, img, g.latent_ch, H, W, tin->cin_pad, n);
+  launch_fill_u16(s, img, (long long)(n + pad_frames) * (H + 2) * (W + 2) * tin->cin_pad, 0);
+  launch_latent_to_image(s, latent, F.frame(H, W, tin->cin_pad), g.latent_ch, H, W, tin->cin_pad, n, g.temporal ? n : 0);
   F.conv3("conv_in", img, H, W, OUT_F32, xa, C0);
   // mid block
   F.res("mid.res0", xa, xa, H, W, C0, C0);
@@ -479,10 +507,12 @@ dit_status dec_forward(dec_ctx* c, int n, int h, int w, const float* latent, flo
       else F.res(name, x, x, H, W, ch, ch);
     }
     prev = ch;
-    DTAP("up" + std::to_string(l), x, (size_t)n * H * W * ch * 4);
+    DTAP("up" + std::to_string(l), x, (size_t)F.B * H * W * ch * 4);
     if (l != g.n_levels - 1) {
-      launch_zero_border(s, img, 2 * H, 2 * W, ch, n);
-      launch_upsample_pad(s, x, img, H, W, ch, n);
+      const int frame_up = g.temporal && l < g.t_up;       // F frames -> 2F - 1: the first once, the others twice
+      if (frame_up) F.B = 2 * F.B - 1;
+      F.zero_img(2 * H, 2 * W, ch);
+      launch_upsample_pad(s, x, F.frame(2 * H, 2 * W, ch), H, W, ch, F.B, frame_up);
       H *= 2; W *= 2;
       F.conv3("up" + std::to_string(l) + ".upconv", img, H, W, OUT_F32, other, ch);
       std::swap(x, other);
@@ -490,12 +520,13 @@ dit_status dec_forward(dec_ctx* c, int n, int h, int w, const float* latent, flo
   }
   // output: GN + SiLU + conv to out_ch channels
   F.zero_img(H, W, prev);
-  F.gn("out.gn", x, img, H, W, prev, 1, 1);
+  F.gn("out.gn", x, F.frame(H, W, prev), H, W, prev, 1, 1);
   {
     const DTensor* to = find(c, "conv_out.w");
-    if (!launch_conv3_small(s, img, Wm(c, "conv_out.w"), to->ld, Wv(c, "conv_out.b"), image, H, W, to->cin_pad, g.out_ch, n)) {
-      F.conv3("conv_out", img, H, W, OUT_F32, F.at<float>(L.out4), 4, false);     // wide last level: as a product, rows 4 wide, then compacted
-      launch_compact_rows(s, F.at<float>(L.out4), 4, image, (long long)n * H * W, g.out_ch);
+    // (the small-output kernel knows the 9-tap form only; 27 taps and wide last levels go through the product)
+    if (g.temporal || !launch_conv3_small(s, img, Wm(c, "conv_out.w"), to->ld, Wv(c, "conv_out.b"), image, H, W, to->cin_pad, g.out_ch, n)) {
+      F.conv3("conv_out", img, H, W, OUT_F32, F.at<float>(L.out4), 4, false);     // as a product, rows 4 wide, then compacted
+      launch_compact_rows(s, F.at<float>(L.out4), 4, image, (long long)F.B * H * W, g.out_ch);
     }
   }
   DHIP(c, hipGetLastError());

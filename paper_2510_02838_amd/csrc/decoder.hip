@@ -24,7 +24,7 @@ __device__ __forceinline__ long long dst_pixel(int y, int x, int W, int pad) {
 // latents fp32 channels-first [B][C][H][W] -> bf16 bordered channels-last [B][(H+2)(W+2)][Cpad],
 // channels from C on are zero (the border is zero from a fill of the whole buffer by the caller)
 __global__ __launch_bounds__(256) void latent_to_image_kernel(const float* __restrict__ z, bf16_t* __restrict__ out,
-                                                              int C, int H, int W, int Cpad, int B) {
+                                                              int C, int H, int W, int Cpad, int B, int frames) {
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   const long long per = (long long)H * W * C;
   if (i >= per * B) return;
@@ -33,12 +33,12 @@ __global__ __launch_bounds__(256) void latent_to_image_kernel(const float* __res
   const int c = (int)(r % C);
   const long long p = r / C;
   const int y = (int)(p / W), x = (int)(p % W);
-  out[((long long)b * (H + 2) * (W + 2) + dst_pixel(y, x, W, 1)) * Cpad + c] = d_f2bf(z[(((long long)b * C + c) * H + y) * W + x]);
+  out[((long long)b * (H + 2) * (W + 2) + dst_pixel(y, x, W, 1)) * Cpad + c] = d_f2bf(z[(frames ? ((long long)c * frames + b) : ((long long)b * C + c)) * H * W + (long long)y * W + x]);
 }
 
-void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad, int B) {
+void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad, int B, int frames) {
   const long long n = (long long)B * H * W * C;
-  if (n) hipLaunchKernelGGL(latent_to_image_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, z, out, C, H, W, Cpad, B);
+  if (n) hipLaunchKernelGGL(latent_to_image_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, z, out, C, H, W, Cpad, B, frames);
 }
 
 // zero border of a bordered image [(H+2)(W+2)][C]: rows 0 and H+1, columns 0 and W+1
@@ -219,12 +219,12 @@ size_t group_norm_partial_bytes(long long pixels, int C) {
 
 // nearest 2x upsampling of the fp32 stream into a bf16 bordered image: out pixel (y, x) = in (y/2, x/2)
 __global__ __launch_bounds__(256) void upsample_pad_kernel(const float* __restrict__ x, bf16_t* __restrict__ out,
-                                                           int H, int W, int C) {       // H, W: input size
+                                                           int H, int W, int C, int frame_up) {       // H, W: input size
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
   const int qpc = C >> 2;
   const int H2 = 2 * H, W2 = 2 * W;
   if (i >= (long long)H2 * W2 * qpc) return;
-  x += (size_t)blockIdx.y * H * W * C;               // one image per blockIdx.y
+  x += (size_t)(frame_up ? (blockIdx.y + 1) >> 1 : blockIdx.y) * H * W * C;     // one output image per blockIdx.y
   out += (size_t)blockIdx.y * (H2 + 2) * (W2 + 2) * C;
   const long long p = i / qpc;
   const int c = (int)(i % qpc) * 4;
@@ -234,9 +234,9 @@ __global__ __launch_bounds__(256) void upsample_pad_kernel(const float* __restri
   w.x = d_pack2(v.x, v.y); w.y = d_pack2(v.z, v.w);
   *(uint2*)(out + dst_pixel(y, xx, W2, 1) * C + c) = w;
 }
-void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C, int B) {
+void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C, int B, int frame_up) {
   const long long n = (long long)4 * H * W * (C / 4);
-  if (n && B) hipLaunchKernelGGL(upsample_pad_kernel, dim3((unsigned)((n + 255) / 256), B), dim3(256), 0, s, x, out, H, W, C);
+  if (n && B) hipLaunchKernelGGL(upsample_pad_kernel, dim3((unsigned)((n + 255) / 256), B), dim3(256), 0, s, x, out, H, W, C, frame_up);
 }
 
 // fp32 -> bf16, 4 elements per thread (plain rows)

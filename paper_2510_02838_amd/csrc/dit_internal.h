@@ -52,8 +52,10 @@ struct GemmProblem {
   // one-pixel zero border each, [B][(H+2)*(conv_w+2)][conv_cin]; conv_img = H*conv_w pixels per
   // image; row m of the product is pixel (r / conv_w, r % conv_w) of image m / conv_img,
   // r = m % conv_img; column index k = tap*conv_cin + c with tap = 3*ky + kx; conv_cin % 64 == 0,
-  // K = 9*conv_cin.
-  int conv_w = 0, conv_cin = 0, conv_img = 1;
+  // K = 9*conv_cin.  conv_kt = 3: a causal 3x3x3 convolution over a stack of frames: K = 27*conv_cin,
+  // tap = (kf*3 + ky)*3 + kx, and frame tap kf of output frame b reads stack image b + kf, so A starts
+  // with the two (zero) frames before the first.
+  int conv_w = 0, conv_cin = 0, conv_img = 1, conv_kt = 1;
   // convolutions with OUT_F32 / OUT_RESID_F32 only, optional: per column n, the sum and the sum
   // of squares of the stored values over the rows of each (tile row, wave row) pair:
   // stats[(tile_row * 2 + wave_row)][N][2], rows of a pair = tile height / 2 (gemm_stats_rows)
@@ -180,21 +182,23 @@ void launch_rel_bias_table(hipStream_t s, const float* table, float* bias, int H
 
 // ---- Decode stage (convolutional decoder), channels-last activations ----------------------
 // latent fp32 [C][H][W] -> bf16 bordered image [(H+2)(W+2)][Cpad] (interior only; caller zero-fills)
-void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad, int B = 1);
+// frames = 0: z is [B][C][H][W]; frames = B: z is one video [C][B][H][W]
+void launch_latent_to_image(hipStream_t s, const float* z, bf16_t* out, int C, int H, int W, int Cpad, int B = 1, int frames = 0);
 void launch_zero_border(hipStream_t s, bf16_t* img, int H, int W, int C, int B = 1);   // C % 8 == 0
 // GroupNorm (eps 1e-6, affine) of the fp32 stream x [H*W][C], optional SiLU, bf16 output with
 // (pad=1) or without a one-pixel border.  C in {64,128,256,512,1024}; partial: scratch of
 // group_norm_partial_bytes; stats: scratch of GN_STATS_BYTES (groups <= 32).  ready_chunks > 0: partial already holds
 // [ready_chunks][C][2] channel sums of x (GemmProblem::stats) and the statistics pass is skipped.
 size_t group_norm_partial_bytes(long long pixels, int C);
-constexpr int GN_MAX_BATCH = 64;
+constexpr int GN_MAX_BATCH = 128;
 constexpr size_t GN_STATS_HEAD = (size_t)GN_MAX_BATCH * 32 * 8;                       // [B][groups] float2
 constexpr size_t GN_STATS_BYTES = GN_STATS_HEAD + (size_t)GN_MAX_BATCH * 32 * 16 * 16;   // + [B][groups][shares] double2
 void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const float* beta, bf16_t* out,
                        float* partial, float2* stats, int H, int W, int C, int groups, int silu, int pad,
                        int ready_chunks = 0, int B = 1);   // B same-size images back to back, statistics per image
 // nearest 2x upsampling of x [H*W][C] fp32 into a bf16 bordered image of size 2H x 2W
-void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C, int B = 1);
+// B output images; frame_up: output image g shows input image (g + 1) / 2 (frame-rate doubling), else image g
+void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C, int B = 1, int frame_up = 0);
 void launch_cast_bf16(hipStream_t s, const float* x, bf16_t* out, long long n);     // n % 4 == 0
 // out[r][j] = softmax_j(sc[r][j] * scale) as bf16, j < n; columns n..ldo-1 are set to zero
 void launch_softmax_rows(hipStream_t s, const float* sc, int lds_, bf16_t* out, int ldo, int rows, int n, float scale_log2);

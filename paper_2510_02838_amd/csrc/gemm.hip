@@ -246,8 +246,12 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
     const int ks = (kt < nk ? kt : nk - 1) * BKT;
     int ka = ks;             // A-side offset of the slab
     if constexpr (CONV) {    // slab = 64 channels of one tap (ky, kx): shift by ky rows and kx pixels
-      const int tap = ks / P.conv_cin, c0 = ks - tap * P.conv_cin, ky = tap / 3, kx = tap - 3 * ky;
-      ka = (ky * (P.conv_w + 2) + kx) * P.conv_cin + c0;
+      int tap = ks / P.conv_cin;
+      const int c0 = ks - tap * P.conv_cin;
+      int kf = 0;            // 27 taps: the first index is the frame, 0 = two frames back (the stack starts two frames early)
+      if (P.conv_kt == 3) { kf = tap / 9; tap -= 9 * kf; }
+      const int ky = tap / 3, kx = tap - 3 * ky;
+      ka = ((kf * (P.conv_img / P.conv_w + 2) + ky) * (P.conv_w + 2) + kx) * P.conv_cin + c0;
     }
     unsigned char* dB = dA + OFFB;
 #pragma unroll
@@ -923,7 +927,8 @@ int launch_gemm(hipStream_t s, GemmBatch& b, int force_tile) {
   if (conv) {     // convolutions: never mixed with plain products, three tile shapes
     if (plain) return -1;
     for (int i = 0; i < b.n; ++i)        // whole images of whole rows
-      if (b.p[i].conv_img <= 0 || b.p[i].conv_img % b.p[i].conv_w || b.p[i].M % b.p[i].conv_img) return -1;
+      if (b.p[i].conv_img <= 0 || b.p[i].conv_img % b.p[i].conv_w || b.p[i].M % b.p[i].conv_img ||
+          (b.p[i].conv_kt != 1 && b.p[i].conv_kt != 3) || b.p[i].K != 9 * b.p[i].conv_kt * b.p[i].conv_cin) return -1;
     if (tile == 1256256) launch_t<256, 256, 2, 4, 64, 2, 0, true, 3>(s, b);
     else if (tile == 30128128) launch_t<128, 128, 2, 2, 64, 4, 0, true, 2>(s, b);
     else { tile = 128128; launch_t<128, 128, 2, 2, 64, 2, 0, true, 2>(s, b); }

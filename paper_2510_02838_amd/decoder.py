@@ -12,13 +12,14 @@ DEC_MAX_LEVELS = 6
 
 class dec_config(C.Structure):
     _fields_ = [("latent_ch", C.c_int), ("out_ch", C.c_int), ("n_levels", C.c_int),
-                ("channels", C.c_int * DEC_MAX_LEVELS), ("n_res", C.c_int)]
+                ("channels", C.c_int * DEC_MAX_LEVELS), ("n_res", C.c_int), ("temporal", C.c_int), ("t_up", C.c_int)]
 
 
 _SIGS = {
     "dec_create": (_i, [C.POINTER(dec_config), _i, _vp, C.POINTER(_vp)]),
     "dec_destroy": (None, [_vp]),
     "dec_last_error": (C.c_char_p, [_vp]),
+    "dec_frames_out": (_i, [_vp, _i]),
     "dec_weight_bytes": (_sz, [_vp]),
     "dec_workspace_bytes": (_sz, [_vp, _i, _i, _i]),
     "dec_bind": (_i, [_vp, _vp, _sz, _vp, _sz]),
@@ -43,7 +44,8 @@ def make_config(arch):
     if not 1 <= len(ch) <= DEC_MAX_LEVELS:
         raise DitError(1, "1..6 levels")
     arr = (C.c_int * DEC_MAX_LEVELS)(*(ch + [0] * (DEC_MAX_LEVELS - len(ch))))
-    return dec_config(arch["latent_ch"], arch["out_ch"], len(ch), arr, arch["n_res"])
+    # a "t_up" entry makes it the causal video decoder
+    return dec_config(arch["latent_ch"], arch["out_ch"], len(ch), arr, arch["n_res"], int("t_up" in arch), arch.get("t_up", 0))
 
 
 class Decoder:
@@ -85,6 +87,9 @@ class Decoder:
     def workspace_bytes(self, h, w, n=1):
         return dec_workspace_bytes(self.ctx, n, h, w)
 
+    def frames_out(self, n):
+        return dec_frames_out(self.ctx, n)
+
     def up_factor(self):
         return 1 << (self.cfg.n_levels - 1)
 
@@ -123,7 +128,8 @@ class Decoder:
             self.set_tensor(name, arr)
 
     def forward(self, h, w, latent, image, n=1):
-        """latent: fp32 [n][latent_ch][h][w]; image: fp32 [n][h*f][w*f][out_ch], f = up_factor()."""
+        """latent: fp32 [n][latent_ch][h][w]; image: fp32 [n][h*f][w*f][out_ch], f = up_factor().
+        Video decoder: latent [latent_ch][n][h][w] of one video, image [frames_out(n)][h*f][w*f][out_ch]."""
         self.check(dec_forward(self.ctx, n, h, w, latent.data_ptr(), image.data_ptr()))
 
     def set_tap(self, point, tensor):

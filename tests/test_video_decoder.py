@@ -1,0 +1,175 @@
+"""Decode stage, video form (causal 3x3x3 convolutions): host logic without a GPU, and GPU parity
+with the float64 oracle through the C ABI.  Tolerances are the image decoder's: every convolution
+takes its input rounded to bf16 and the residual stream carries those errors on, so rel-L2 1e-2
+in the mid block, 2e-2 for level outputs and frames, max-abs 3e-2 of the largest reference value."""
+import numpy as np
+import pytest
+
+import synth
+from helpers import rel_l2, max_abs
+from oracle import video_decoder_oracle as V
+
+ARCH = synth.VIDEO_DECODERS["vae3d_tiny"]
+
+
+@pytest.fixture(scope="module")
+def X():
+    from paper_2510_02838_amd import decoder
+    return decoder
+
+
+@pytest.fixture(scope="module")
+def torch():
+    import torch
+    torch.cuda.set_device(0)
+    return torch
+
+
+@pytest.mark.parametrize("name", list(synth.VIDEO_DECODERS))
+def test_video_decoder_tensor_table_matches_oracle_parameter_list(X, name):
+    arch = synth.VIDEO_DECODERS[name]
+    m = X.Decoder(arch, bind=False)
+    shapes = V.param_shapes(arch)
+    table = m.tensors()
+    assert [t[0] for t in table] == list(shapes)
+    kinds = {"matrix": 0, "bias": 1, "gain": 2}
+    for tname, r, c, k in table:
+        shape, kind = shapes[tname]
+        assert k == kinds[kind]
+        assert (r, c) == (tuple(shape) if len(shape) == 2 else (1, shape[0]))
+    m.close()
+
+
+def test_video_decoder_frame_counts_sizes_and_bad_configurations(X):
+    m = X.Decoder(ARCH, bind=False)                                  # one frame-rate doubling
+    assert [m.frames_out(n) for n in (1, 2, 3, 13)] == [1, 3, 5, 25] == [V.out_frames(ARCH, n) for n in (1, 2, 3, 13)]
+    assert m.frames_out(0) == 0
+    assert 0 < m.workspace_bytes(16, 16, 2) < m.workspace_bytes(16, 16, 3)
+    assert m.workspace_bytes(8, 8, 1) > 0            # a single frame: the image decoder's granularity
+    assert m.workspace_bytes(8, 8, 2) == 0           # several frames: pixel count a multiple of 256
+    assert m.workspace_bytes(16, 16, 65) == 0        # 129 output frames
+    m.close()
+    two = X.Decoder(dict(ARCH, t_up=2), bind=False)
+    assert two.frames_out(13) == 49
+    two.close()
+    img = X.Decoder(synth.DECODERS["ae_tiny"], bind=False)
+    assert img.frames_out(7) == 7
+    img.close()
+    for bad in (dict(ARCH, t_up=3), dict(ARCH, t_up=-1)):
+        with pytest.raises(Exception):
+            X.Decoder(bad, bind=False)
+
+
+# --------------------------------------------------------------------------------- GPU
+def _params(arch, seed=1):
+    p = synth.make_params(V.param_shapes(arch), seed, 0.02, 0.02, 0.1)
+    for n, v in p.items():                           # 27 taps: keep the layer gain of the 9-tap decoder's recipe
+        if v.ndim == 2 and v.shape[0] % 27 == 0 and not n.startswith("mid.attn."):
+            p[n] = synth.round_bf16(v / np.sqrt(3.0))
+    for n in ("mid.attn.q.w", "mid.attn.k.w"):       # logits of a few units: a softmax that is far from uniform
+        p[n] = p[n] * 8.0
+    return p
+
+
+def _latent(arch, F, h, w, seed=3):
+    c = arch["latent_ch"]
+    return synth.gaussian(seed, "video latent", c * F * h * w).astype(np.float32).reshape(c, F, h, w)
+
+
+def _run(torch, X, arch, params, z, taps=(), model=None):
+    c, F, h, w = z.shape
+    m = model or X.Decoder(arch)
+    m.ensure_workspace(h, w, F)
+    if model is None:
+        m.init_weights(0, 0.0)
+        m.set_params(params)
+    f, Fo = m.up_factor(), m.frames_out(F)
+    bufs = {}
+    frames = F
+    for l in range(len(arch["channels"])):
+        name = f"up{l}"
+        if name in taps:
+            bufs[name] = torch.zeros((frames * h * w * 4 ** l, arch["channels"][l]), dtype=torch.float32, device="cuda")
+        if l < arch["t_up"]:
+            frames = 2 * frames - 1
+    for name in taps:
+        if not name.startswith("up"):
+            bufs[name] = torch.zeros((F * h * w, arch["channels"][0]), dtype=torch.float32, device="cuda")
+    for name, b in bufs.items():
+        m.set_tap(name, b)
+    out = torch.full((Fo, h * f, w * f, arch["out_ch"]), float("nan"), dtype=torch.float32, device="cuda")
+    m.forward(h, w, torch.from_numpy(z).cuda(), out, F)
+    torch.cuda.synchronize()
+    m.clear_taps()
+    return m, out.cpu().numpy(), {k: v.cpu().numpy() for k, v in bufs.items()}
+
+
+def _check_video(got, ref):
+    assert got.shape == ref.shape and np.isfinite(got).all()
+    assert rel_l2(got, ref) <= 2e-2, rel_l2(got, ref)
+    assert max_abs(got, ref) <= 3e-2 * max(1.0, np.abs(ref).max()), max_abs(got, ref)
+    for g in range(ref.shape[0]):                    # no frame hides behind the others
+        assert rel_l2(got[g], ref[g]) <= 3e-2, (g, rel_l2(got[g], ref[g]))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("shape", [(3, 16, 16), (2, 16, 32), (1, 8, 8), (1, 4, 48)])
+def test_video_decoder_forward_and_intermediates_against_oracle(torch, X, shape):
+    F, h, w = shape
+    params = _params(ARCH)
+    z = _latent(ARCH, F, h, w)
+    names = ["mid.res0", "mid.attn"] + [f"up{l}" for l in range(len(ARCH["channels"]))]
+    m, got, taps = _run(torch, X, ARCH, params, z, names)
+    ref_taps = {}
+    ref = V.VideoDecoderOracle(ARCH, params).forward(np.transpose(z, (1, 2, 3, 0)), ref_taps)
+    for name in names:
+        r = ref_taps[name].reshape(-1, ref_taps[name].shape[-1])
+        print(name, "rel-L2 %.2e" % rel_l2(taps[name], r))
+        assert taps[name].shape == r.shape
+        assert rel_l2(taps[name], r) <= (1e-2 if name.startswith("mid") else 2e-2), (name, rel_l2(taps[name], r))
+    print("video rel-L2 %.2e max-abs %.2e of %.2f" % (rel_l2(got, ref), max_abs(got, ref), np.abs(ref).max()))
+    _check_video(got, ref)
+    m.close()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("t_up", [0, 2])
+def test_video_decoder_no_and_two_frame_rate_doublings(torch, X, t_up):
+    arch = dict(ARCH, t_up=t_up)
+    params = _params(arch, seed=5)
+    z = _latent(arch, 3, 16, 16, seed=6)
+    m, got, _ = _run(torch, X, arch, params, z)
+    assert got.shape[0] == (3, 5, 9)[t_up]
+    _check_video(got, V.VideoDecoderOracle(arch, params).forward(np.transpose(z, (1, 2, 3, 0))))
+    m.close()
+
+
+@pytest.mark.gpu
+def test_video_decoder_is_causal_bit_for_bit(torch, X):
+    """A change of the last latent frame leaves every output frame before the first one that shows
+    it exactly as it was, and changes the others; a one-frame video through a decoder without the
+    two earlier frame taps is the image decoder's result."""
+    params = _params(ARCH, seed=7)
+    z = _latent(ARCH, 3, 16, 16, seed=8)
+    m, a, _ = _run(torch, X, ARCH, params, z)
+    z2 = z.copy(); z2[:, 2] += 0.5
+    _, b, _ = _run(torch, X, ARCH, params, z2, model=m)
+    assert np.array_equal(a[:3], b[:3]) and not np.allclose(a[3], b[3]) and not np.allclose(a[4], b[4])
+    # fewer frames of the same video: the common frames do not move (nothing looks ahead)
+    _, c, _ = _run(torch, X, ARCH, params, np.ascontiguousarray(z[:, :2]), model=m)
+    assert c.shape[0] == 3 and np.array_equal(c, a[:3])
+    m.close()
+
+
+@pytest.mark.gpu
+def test_video_decoder_wide_configuration_against_oracle(torch, X):
+    """Benchmark widths (512..128 channels, 1x1 shortcuts where the width drops, two frame-rate
+    doublings), one residual block per level so that the float64 reference stays within seconds:
+    2 latent frames of 16 x 16 -> 5 frames of 128 x 128 (81920 product rows, K up to 13824)."""
+    arch = dict(synth.VIDEO_DECODERS["vae3d"], n_res=1)
+    params = _params(arch, seed=2)
+    z = _latent(arch, 2, 16, 16)
+    m, got, _ = _run(torch, X, arch, params, z)
+    assert got.shape == (5, 128, 128, 3)
+    _check_video(got, V.VideoDecoderOracle(arch, params).forward(np.transpose(z, (1, 2, 3, 0))))
+    m.close()
