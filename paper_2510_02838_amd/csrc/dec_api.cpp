@@ -115,10 +115,12 @@ struct Layout {
 constexpr size_t PARTIAL_BYTES = (size_t)256 * 128 * 128 * 4;
 
 // latent sides 1..4096, h*w a multiple of 64 (whole k-slabs in the attention products) and at
-// most 65536 (the score matrix is held whole); the final image at most 65535 rows and, as a
-// stack of n bordered images of the widest level, below 2^32 elements (32-bit offsets in the
-// kernels); n images: 1..GN_MAX_BATCH, and with n > 1 h*w a multiple of 256 (group-norm chunks
-// must not straddle images)
+// most 65536 (the score matrix is held whole); the final image at most 65535 rows, all output
+// pixels together below 2^29 (product rows are 32-bit), and what one tile of a convolution
+// reaches in its stack of bordered images (its own rows' windows plus the taps: an image, or three
+// frames of a video) below 2^31 elements (32-bit byte offsets from the tile's first window);
+// n images: 1..GN_MAX_BATCH, and with n > 1 h*w a multiple of 256 (group-norm chunks must not
+// straddle images)
 // frames (images) at the output of a video decoder that starts with n: 2F - 1 per frame-rate doubling
 long long frames_out(const dec_ctx* c, long long n) {
   if (c->cfg.temporal)
@@ -132,21 +134,17 @@ bool size_ok(const dec_ctx* c, int n, int h, int w) {
   const int up = 1 << (c->cfg.n_levels - 1);
   const long long Hf = (long long)h * up, Wf = (long long)w * up;
   if (Hf > 65535 || nf * Hf * Wf >= (1LL << 31) / 4) return false;
-  // the widest bordered stack of each level: its own width, and the previous level's after the upsampling
-  // (a video's stacks start with two zero frames)
-  const long long pad = c->cfg.temporal ? 2 : 0;
-  long long H = h, W = w, worst = 0, F = n;
+  // the widest bordered image of each level: its own width, and the previous level's after the upsampling
+  const long long reach = c->cfg.temporal ? 3 : 1;
+  long long H = h, W = w, worst = 0;
   int prev = std::max(c->cfg.channels[0], 64);
   for (int l = 0; l < c->cfg.n_levels; ++l) {
     const int ch = c->cfg.channels[l];
-    worst = std::max(worst, (F + pad) * (H + 2) * (W + 2) * std::max(ch, prev));
+    worst = std::max(worst, reach * (H + 2) * (W + 2) * std::max(ch, prev));
     prev = ch;
-    if (l != c->cfg.n_levels - 1) {
-      if (c->cfg.temporal && l < c->cfg.t_up) F = 2 * F - 1;
-      H *= 2; W *= 2; worst = std::max(worst, (F + pad) * (H + 2) * (W + 2) * ch);
-    }
+    if (l != c->cfg.n_levels - 1) { H *= 2; W *= 2; worst = std::max(worst, reach * (H + 2) * (W + 2) * ch); }
   }
-  return worst < (1LL << 32);
+  return worst < (1LL << 31);
 }
 
 void plan(const dec_ctx* c, int n, int h, int w, Layout& L) {
@@ -439,7 +437,7 @@ dit_status dec_forward(dec_ctx* c, int n, int h, int w, const float* latent, flo
   if (!latent || !image) return dfail(c, DIT_EINVAL, "null latent or image");
   if (!size_ok(c, n, h, w))
     return dfail(c, DIT_ESHAPE, "%d latent(s) of %d x %d: sides 1..4096, pixel count a multiple of 64 (256 for a batch or a video) and at most 65536, "
-                 "1..%d images or output frames, their bordered stack below 2^32 elements per level", n, h, w, GN_MAX_BATCH);
+                 "1..%d images or output frames with fewer than 2^29 pixels together", n, h, w, GN_MAX_BATCH);
   const dec_config& g = c->cfg;
   DHIP(c, hipSetDevice(c->device));
   Layout L;

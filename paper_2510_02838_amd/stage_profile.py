@@ -26,6 +26,8 @@ each for the stages before and after it:
 
     python -m paper_2510_02838_amd.stage_profile encode [--encoder t5_xxl] [--lens 32,128,500] [--max-batch 64]
     python -m paper_2510_02838_amd.stage_profile decode [--decoder ae_kl] [--res 128,256,512,1024] [--max-batch 8]
+    python -m paper_2510_02838_amd.stage_profile decode --decoder vae3d [--res 256x384,512x768] [--frames 1,5,13]
+          (the causal video decoder, one video per call: latency against the number of latent frames)
     python -m paper_2510_02838_amd.stage_profile pipeline [--workload sd3|flux] [--res 512,1024] [--steps 28] [--overlap N]
 
   pipeline  one request through all three stages on this GPU, the output of each feeding the next
@@ -237,10 +239,85 @@ def decoder_flops(arch, h, w):
     return total + conv(px, ch[-1], arch["out_ch"], 3)
 
 
+def video_decoder_flops(arch, F, h, w):
+    """Multiply-add flops (2 per MAC) of the products of one decode of F latent frames of h x w by
+    the causal video decoder: 27 taps per 3x3x3 convolution, frame count doubling (2F - 1) at the
+    first t_up level transitions."""
+    ch = arch["channels"]
+    conv = lambda px, cin, cout, taps: 2.0 * px * taps * cin * cout
+    res = lambda px, cin, cout: conv(px, cin, cout, 27) + conv(px, cout, cout, 27) + (conv(px, cin, cout, 1) if cin != cout else 0.0)
+    px = F * h * w
+    total = conv(px, arch["latent_ch"], ch[0], 27) + 2 * res(px, ch[0], ch[0])
+    total += 4 * conv(px, ch[0], ch[0], 1) + F * 4.0 * (h * w) ** 2 * ch[0]   # q, k, v, proj; per-frame scores and weighted sum
+    prev = ch[0]
+    for l, c in enumerate(ch):
+        for r in range(arch["n_res"]):
+            total += res(px, prev if r == 0 else c, c)
+        prev = c
+        if l != len(ch) - 1:
+            if l < arch["t_up"]:
+                F = 2 * F - 1
+            h, w = 2 * h, 2 * w
+            px = F * h * w
+            total += conv(px, c, c, 27)
+    return total + conv(px, ch[-1], arch["out_ch"], 27)
+
+
+def run_decode_video(args):
+    """One video per call: latency against the number of latent frames, per frame size."""
+    import torch
+    import synth
+    from . import decoder as X
+    arch = synth.VIDEO_DECODERS[args.decoder]
+    m = X.Decoder(arch)
+    f = m.up_factor()
+    sizes = [tuple(int(v) // f for v in r.split("x")) for r in args.res.split(",")]
+    frames = [int(v) for v in args.frames.split(",")]
+    rows = []
+    first = True
+    for h, w in sizes:
+        for F in frames:
+            ws = m.workspace_bytes(h, w, F)
+            if ws == 0:                                   # more than 128 output frames or 2^29 output pixels
+                continue
+            m.ensure_workspace(h, w, F)
+            if first:
+                m.init_weights(1, 0.02)
+                first = False
+            Fo = m.frames_out(F)
+            z = torch.from_numpy(synth.gaussian(3, "video latent", arch["latent_ch"] * F * h * w).astype(np.float32)).cuda()
+            out = torch.empty((Fo, h * f, w * f, arch["out_ch"]), dtype=torch.float32, device="cuda")
+            m.forward(h, w, z, out, n=F)
+            torch.cuda.synchronize()
+            best = float("inf")
+            for _ in range(3):
+                t0 = time.perf_counter()
+                m.forward(h, w, z, out, n=F)
+                torch.cuda.synchronize()
+                best = min(best, time.perf_counter() - t0)
+            if not bool(torch.isfinite(out).all().item()):
+                raise RuntimeError("non-finite video")
+            fl = video_decoder_flops(arch, F, h, w)
+            row = {"table": "decode_video", "decoder": args.decoder, "height": h * f, "width": w * f, "latent_frames": F,
+                   "frames": Fo, "ms": best * 1e3, "ms_per_frame": best * 1e3 / Fo, "product_flops": fl,
+                   "tflops": fl / best / 1e12, "workspace_bytes": ws, "weight_bytes": m.weight_bytes()}
+            rows.append(row)
+            print(json.dumps(row), flush=True)
+            del z, out
+    print("| video | latent frames -> frames | TFLOP | ms | TFLOP/s | ms per frame | workspace GiB |", file=sys.stderr)
+    print("|---|---|---|---|---|---|---|", file=sys.stderr)
+    for r in rows:
+        print(f"| {r['height']}x{r['width']} | {r['latent_frames']} -> {r['frames']} | {r['product_flops'] / 1e12:.1f} | {r['ms']:.1f} | "
+              f"{r['tflops']:.0f} | {r['ms_per_frame']:.2f} | {r['workspace_bytes'] / 2**30:.2f} |", file=sys.stderr)
+    print(f"weights {m.weight_bytes() / 2**20:.0f} MiB", file=sys.stderr)
+
+
 def run_decode(args):
     import torch
     import synth
     from . import decoder as X
+    if args.decoder in synth.VIDEO_DECODERS:
+        return run_decode_video(args)
     arch = synth.DECODERS[args.decoder]
     m = X.Decoder(arch)
     f = m.up_factor()
@@ -252,7 +329,7 @@ def run_decode(args):
         lat = {}
         for b in batches:
             ws = m.workspace_bytes(n, n, b)
-            if ws == 0:                                   # the batch form needs h*w % 256 == 0 and 32-bit offsets
+            if ws == 0:                                   # the batch form needs h*w % 256 == 0 and fewer than 2^29 output pixels
                 continue
             m.ensure_workspace(n, n, b)
             if first:
@@ -428,7 +505,8 @@ DEFAULT_RES = {
 def main():
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     ap.add_argument("table", choices=["batch", "grid", "encode", "decode", "pipeline"])
-    ap.add_argument("--decoder", default="ae_kl", choices=["ae_kl", "ae_tiny"])
+    ap.add_argument("--decoder", default="ae_kl", choices=["ae_kl", "ae_tiny", "vae3d", "vae3d_tiny"])
+    ap.add_argument("--frames", default="1,5,13", help="decode with a video decoder: latent frames per video")
     ap.add_argument("--encoder", default="t5_xxl", choices=["t5_xxl", "t5_tiny"])
     ap.add_argument("--lens", default="32,128,500")
     ap.add_argument("--workload", default="sd3", choices=["sd3", "flux", "wan", "tiny"])
@@ -442,7 +520,7 @@ def main():
     if args.table == "encode":
         return run_encode(args)
     if args.table == "decode":
-        args.res = args.res or "128,256,512,1024"
+        args.res = args.res or ("256x384,512x768" if args.decoder.startswith("vae3d") else "128,256,512,1024")
         return run_decode(args)
     if args.table == "pipeline":
         args.res = args.res or "512,1024"
