@@ -461,7 +461,8 @@ __global__ __launch_bounds__(WM * WN * 64) void gemm_kernel(const GemmBatch batc
               for (int c = 0; c < 4; ++c) { cs[c] += x4[c]; cq[c] += x4[c] * x4[c]; }
             }
           } else {
-            const float* gp = P.gate ? P.gate + (size_t)rq[it] * P.gate_stride + n : nullptr;
+            // (ragged last columns: the request index is read here, rq[] may already hold the next patch's)
+            const float* gp = P.gate ? P.gate + (size_t)(P.row_req ? P.row_req[m] : 0) * P.gate_stride + n : nullptr;
             for (int c = 0; c < VEC && n + c < P.N; ++c) {
               const float r = xp[c] + (gp ? gp[c] : 1.f) * v[c];
               xp[c] = r;

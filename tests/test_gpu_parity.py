@@ -128,21 +128,28 @@ def test_gemm_seeded_random_shapes(torch, B):
         assert np.isfinite(got).all() and err.max() <= tol, (case, M, N, K, kind, err.max())
 
 
-def test_gemm_gated_residual_epilogue(torch, B):
-    M, N, K, n_req = 333, 512, 128, 3
+@pytest.mark.parametrize("M,N,K", [(333, 512, 128), (300, 130, 320), (517, 1030, 192)])
+def test_gemm_gated_residual_epilogue(torch, B, M, N, K):
+    """x += gate[request of the row] * (A W^T + b); the requests change inside tiles, and with N = 130
+    and 1030 the last columns of a row take the element-wise path of the epilogue."""
+    n_req = 3
     A, W = rnd(1, "A", (M, K)), rnd(2, "W", (N, K), 0.05)
-    bias, gate = rnd(3, "b", (N,), 0.5), synth.gaussian(4, "g", n_req * 700).reshape(n_req, 700)
+    gs = (N + 191) // 4 * 4                               # gate rows start 16-byte aligned
+    bias, gate = rnd(3, "b", (N,), 0.5), synth.gaussian(4, "g", n_req * gs).reshape(n_req, gs)
     x0 = synth.gaussian(5, "x", M * N).reshape(M, N)
     row_req = (np.arange(M) * n_req // M).astype(np.int32)
-    dA, dW = to_dev_bf16(torch, A), to_dev_bf16(torch, W)
-    dx = torch.from_numpy(x0.copy()).cuda()
+    npad, ldc = (N + 255) // 256 * 256, (N + 3) // 4 * 4
+    Wp = np.zeros((npad, K), np.float32); Wp[:N] = W
+    dA, dW = to_dev_bf16(torch, A), to_dev_bf16(torch, Wp)
+    dx = torch.zeros((M, ldc), dtype=torch.float32, device="cuda")
+    dx[:, :N] = torch.from_numpy(x0).cuda()
     dg, db, dr = torch.from_numpy(gate).cuda(), torch.from_numpy(bias).cuda(), torch.from_numpy(row_req).cuda()
-    st = B.dit_op_gemm(None, dA.data_ptr(), K, dW.data_ptr(), K, db.data_ptr(), M, N, K, 3, dx.data_ptr(), N,
-                       dg[:, 100:].data_ptr(), 700, dr.data_ptr())
+    st = B.dit_op_gemm(None, dA.data_ptr(), K, dW.data_ptr(), K, db.data_ptr(), M, N, K, 3, dx.data_ptr(), ldc,
+                       dg[:, 100:].data_ptr(), gs, dr.data_ptr())
     assert st == 0
     torch.cuda.synchronize()
     ref = x0 + gate[row_req][:, 100:100 + N].astype(np.float64) * (A.astype(np.float64) @ W.astype(np.float64).T + bias)
-    assert max_abs(dx.cpu().numpy(), ref) < 1e-4
+    assert max_abs(dx[:, :N].cpu().numpy(), ref) < 1e-4
 
 
 @pytest.mark.parametrize("M,N,K,splits", [(218, 384, 1536, 6), (64, 1000, 6144, 7), (1, 256, 64, 1), (300, 130, 320, 5),

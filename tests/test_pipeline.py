@@ -57,3 +57,41 @@ def test_encode_diffuse_decode_chain_against_the_oracle_chain():
     assert np.isfinite(got).all()
     assert rel_l2(got, img_ref) <= 8e-2, rel_l2(got, img_ref)
     enc.close(); dec.close()
+
+
+@pytest.mark.gpu
+def test_video_diffuse_decode_chain_against_the_oracle_chain():
+    """The video family: T denoising steps of a small model with self- and cross-attention blocks
+    leave a [C][F][h][w] latent on the device, which the causal video decoder turns into frames
+    (3 latent frames -> 5 frames), against the chain of the two float64 oracles."""
+    import torch
+    from oracle import video_decoder_oracle as V
+    from paper_2510_02838_amd import binding as B, decoder as XD
+    torch.cuda.set_device(0)
+    arch = dict(family="W", n_blocks=2, n_single=0, hidden=256, n_heads=2, head_dim=128, mlp_hidden=768,
+                latent_ch=16, patch=(1, 2, 2), cond_dim=128, rope_axes=(44, 42, 42), rope_theta=10000.0)
+    reqs, steps = [(3, 16, 16, 40)], 4
+    F, h, w, n_cond = reqs[0]
+    dec_arch = synth.VIDEO_DECODERS["vae3d_tiny"]
+    assert dec_arch["latent_ch"] == arch["latent_ch"]
+    pd = synth.make_params(O.param_shapes(arch), 1, 0.06, 0.1, 0.2)
+    pc = synth.make_params(V.param_shapes(dec_arch), 1, 0.012, 0.02, 0.1)
+    lat, conds, sigmas = synth.make_inputs(reqs, arch["latent_ch"], arch["cond_dim"], steps, [3.0])
+
+    dit = B.DiT(arch); dit.ensure_workspace(reqs, steps); dit.init_weights(0, 0.0); dit.set_params(pd)
+    dec = XD.Decoder(dec_arch); dec.ensure_workspace(h, w, F); dec.init_weights(0, 0.0); dec.set_params(pc)
+    x = torch.from_numpy(lat[0].astype(np.float32).ravel()).cuda()
+    cond = torch.from_numpy(conds[0]).to(torch.bfloat16).cuda()
+    dit.sample(reqs, x, cond, sigmas)
+    up, Fo = dec.up_factor(), dec.frames_out(F)
+    video = torch.full((Fo, h * up, w * up, 3), float("nan"), dtype=torch.float32, device="cuda")
+    dec.forward(h, w, x, video, F)
+    torch.cuda.synchronize()
+
+    x_ref = O.DiTOracle(arch, pd).sample(lat[0], conds[0], sigmas[0])
+    video_ref = V.VideoDecoderOracle(dec_arch, pc).forward(np.transpose(x_ref, (1, 2, 3, 0)))
+    assert rel_l2(x.cpu().numpy().reshape(x_ref.shape), x_ref) <= 5e-2
+    got = video.cpu().numpy()
+    assert got.shape == video_ref.shape == (5, 64, 64, 3) and np.isfinite(got).all()
+    assert rel_l2(got, video_ref) <= 8e-2, rel_l2(got, video_ref)
+    dec.close()
