@@ -99,14 +99,15 @@ def test_gemm_against_float64_matmul(torch, B, M, N, K, variant):
 
 
 def test_gemm_seeded_random_shapes(torch, B):
-    """Forty seeded shapes (M 1..900, N 1..900, K a multiple of 64 up to 2048), each with a seeded
-    output kind, through the launcher's own tile choice: ragged tiles in both directions, the
-    small-M path with and without split-K, the 128- and 256-wide tiles."""
+    """Sixty seeded shapes (M 1..900, N 1..900, K a multiple of 64 up to 2048), each with a seeded
+    output kind (bf16, fp32, GELU, or the gated residual with 1-5 requests whose rows change
+    anywhere, with or without a gate), through the launcher's own tile choice: ragged tiles in both
+    directions, the small-M path, the 128- and 256-wide tiles."""
     rng = np.random.default_rng(12345)
-    for case in range(40):
+    for case in range(60):
         M, N = int(rng.integers(1, 901)), int(rng.integers(1, 901))
         K = 64 * int(rng.integers(1, 33))
-        kind = int(rng.integers(0, 3))
+        kind = int(rng.integers(0, 3)) if case < 40 else 3
         A = rnd(10 + case, "A", (M, K))
         W = rnd(60 + case, "W", (N, K), 0.05)
         bias = rnd(110 + case, "b", (N,), 0.5)
@@ -114,6 +115,26 @@ def test_gemm_seeded_random_shapes(torch, B):
         Wp = np.zeros((npad, K), np.float32); Wp[:N] = W
         dA, dW, dB = to_dev_bf16(torch, A), to_dev_bf16(torch, Wp), torch.from_numpy(bias).cuda()
         ldc = (N + 7) // 8 * 8                       # row stride: a multiple of 16 bytes
+        ref = A.astype(np.float64) @ W.astype(np.float64).T + bias
+        if kind == 3:
+            n_req = int(rng.integers(1, 6))
+            gated = bool(rng.integers(0, 2))
+            cuts = np.sort(rng.integers(0, M + 1, n_req - 1))
+            row_req = np.searchsorted(cuts, np.arange(M), side="right").astype(np.int32)
+            gate = synth.gaussian(200 + case, "g", n_req * ldc).reshape(n_req, ldc)
+            x0 = synth.gaussian(300 + case, "x", M * ldc).reshape(M, ldc)
+            out = torch.from_numpy(x0.copy()).cuda()
+            dg, dr = torch.from_numpy(gate).cuda(), torch.from_numpy(row_req).cuda()
+            st = B.dit_op_gemm(None, dA.data_ptr(), K, dW.data_ptr(), K, dB.data_ptr(), M, N, K, 3, out.data_ptr(), ldc,
+                               dg.data_ptr() if gated else None, ldc, dr.data_ptr())
+            assert st == 0, (case, M, N, K, kind)
+            torch.cuda.synchronize()
+            full = out.cpu().numpy()
+            assert np.array_equal(full[:, N:], x0[:, N:])          # columns past N are left alone
+            want = x0[:, :N] + (gate[row_req][:, :N].astype(np.float64) if gated else 1.0) * ref
+            err = np.abs(full[:, :N] - want) / (np.abs(want) + 1.0)
+            assert err.max() <= 1e-4, (case, M, N, K, n_req, gated, err.max())
+            continue
         out = torch.full((M, ldc), float("nan"), dtype=torch.float32 if kind == 1 else torch.bfloat16, device="cuda")
         st = B.dit_op_gemm(None, dA.data_ptr(), K, dW.data_ptr(), K, dB.data_ptr(), M, N, K, kind, out.data_ptr(), ldc, None, 0, None)
         assert st == 0, (case, M, N, K, kind)
@@ -121,7 +142,6 @@ def test_gemm_seeded_random_shapes(torch, B):
         full = out.to(torch.float32).cpu().numpy()
         assert np.isnan(full[:, N:]).all()           # columns past N are not written
         got = full[:, :N]
-        ref = A.astype(np.float64) @ W.astype(np.float64).T + bias
         want = O.gelu_tanh(ref) if kind == 2 else ref
         tol = 1e-4 if kind == 1 else 2.0 ** -8
         err = np.abs(got - want) / (np.abs(want) + 1.0)
