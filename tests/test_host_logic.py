@@ -166,3 +166,13 @@ def test_profiler_tool_host_logic():
     lvl1 = 2.0 * (4 * px) * 9 * (c * 64 + 64 * 64) + 2.0 * (4 * px) * c * 64
     want2 = want - conv(c, 3, 3) + up + lvl1 + 2.0 * (4 * px) * 9 * 64 * 3
     assert SP.decoder_flops(arch2, 4, 4) == want2
+    # video decoder: 27 taps, frames as pixels; with one frame-rate doubling 3 frames become 5 before
+    # the upsampling convolution; the per-frame attention does not grow with the frame count squared
+    v1 = dict(arch, t_up=0)
+    want_v = 3 * (3 * (conv(4, c, 3) + 3 * 2 * conv(c, c, 3) + conv(c, 3, 3)) + 4 * conv(c, c, 1) + 4.0 * px * px * c)
+    assert SP.video_decoder_flops(v1, 3, 4, 4) == want_v
+    v2 = dict(arch2, t_up=1)
+    lvl0 = 3 * (3 * (conv(4, c, 3) + 3 * 2 * conv(c, c, 3)) + 4 * conv(c, c, 1) + 4.0 * px * px * c)
+    px1 = 5 * 4 * px
+    want_v2 = lvl0 + 2.0 * px1 * 27 * c * c + 2.0 * px1 * 27 * (c * 64 + 64 * 64) + 2.0 * px1 * c * 64 + 2.0 * px1 * 27 * 64 * 3
+    assert SP.video_decoder_flops(v2, 3, 4, 4) == want_v2
