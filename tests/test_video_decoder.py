@@ -196,3 +196,73 @@ def test_video_decoder_benchmark_shape_shorter_video_gives_the_same_first_frames
     assert rel_l2(short, long[:9]) <= 1e-4, rel_l2(short, long[:9])
     assert not np.allclose(long[8], long[9], atol=1e-3 * np.abs(long).max())      # later frames are their own
     m.close()
+
+
+@pytest.mark.gpu
+def test_video_decoder_difference_is_storage_rounding(torch, X):
+    """As for the image decoder: with the reference rounding product operands to bf16 where a 16-bit
+    implementation stores them, and each segment of the network continued from the library's own
+    captured stream, what remains (fp32 accumulation over up to 27 x 128 terms, hardware exp and
+    reciprocal, roundings that flip) is far below the tolerance of the plain comparison."""
+    from oracle import decoder_oracle as D
+    params = _params(ARCH, seed=11)
+    F, h, w = 3, 16, 16
+    z = _latent(ARCH, F, h, w, seed=12)
+    ch = ARCH["channels"]
+    names = ["mid.res0", "mid.attn"] + [f"up{l}" for l in range(len(ch))]
+    m, got, taps = _run(torch, X, ARCH, params, z, names)
+    st = lambda x: synth.round_bf16(x).astype(np.float64)
+
+    class StoredOracle(V.VideoDecoderOracle):
+        """Operands of every product rounded to bf16 (convolution inputs; q, k, v and the softmax
+        weights); this knowledge of the implementation belongs to this test, not to the reference."""
+
+        def conv3(self, name, x):
+            return V.conv3d_causal(st(x), self.p[name + ".w"], self.p[name + ".b"])
+
+        def conv1(self, name, x):
+            return st(x) @ self.p[name + ".w"] + self.p[name + ".b"]
+
+        def attn(self, x):
+            Fn, H, W, C = x.shape
+            hh = self.gn("mid.attn.gn", x)
+            out = []
+            for f in range(Fn):
+                q, k, v = (st(self.conv1("mid.attn." + n, hh[f]).reshape(H * W, C)) for n in ("q", "k", "v"))
+                out.append((st(D.softmax_rows(q @ k.T / np.sqrt(C))) @ v).reshape(H, W, C))
+            return x + self.conv1("mid.attn.proj", np.stack(out))
+
+    ora = StoredOracle(ARCH, params)
+
+    def stream(name, frames, hh, ww, c):
+        return taps[name].astype(np.float64).reshape(frames, hh, ww, c)
+
+    def level(l, x):
+        if l > 0:
+            if l - 1 < ARCH["t_up"]:
+                x = V.upsample_frames(x)
+            x = ora.conv3(f"up{l - 1}.upconv", np.stack([D.upsample2(f) for f in x]))
+        for r in range(ARCH["n_res"]):
+            x = ora.res(f"up{l}.res{r}", x)
+        return x
+
+    seg = {}
+    seg["mid.res0"] = ora.res("mid.res0", ora.conv3("conv_in", np.transpose(z, (1, 2, 3, 0)).astype(np.float64)))
+    seg["mid.attn"] = ora.attn(stream("mid.res0", F, h, w, ch[0]))
+    seg["up0"] = level(0, ora.res("mid.res1", stream("mid.attn", F, h, w, ch[0])))
+    frames = F
+    for l in range(1, len(ch)):
+        f = 2 ** (l - 1)
+        seg[f"up{l}"] = level(l, stream(f"up{l - 1}", frames, h * f, w * f, ch[l - 1]))
+        if l - 1 < ARCH["t_up"]:
+            frames = 2 * frames - 1
+    f = 2 ** (len(ch) - 1)
+    top = stream(f"up{len(ch) - 1}", frames, h * f, w * f, ch[-1])
+    video = ora.conv3("conv_out", D.silu(ora.gn("out.gn", top)))
+    for name in names:
+        r = seg[name].reshape(-1, seg[name].shape[-1])
+        print(name, "segment rel-L2 %.2e" % rel_l2(taps[name], r))
+        assert rel_l2(taps[name], r) <= 2.5e-3, (name, rel_l2(taps[name], r))
+    print("video segment rel-L2 %.2e" % rel_l2(got, video))
+    assert rel_l2(got, video) <= 2.5e-3
+    m.close()
