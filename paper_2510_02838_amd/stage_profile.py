@@ -29,6 +29,7 @@ each for the stages before and after it:
     python -m paper_2510_02838_amd.stage_profile decode --decoder vae3d [--res 256x384,512x768] [--frames 1,5,13]
           (the causal video decoder, one video per call: latency against the number of latent frames)
     python -m paper_2510_02838_amd.stage_profile pipeline [--workload sd3|flux] [--res 512,1024] [--steps 28] [--overlap N]
+    python -m paper_2510_02838_amd.stage_profile pipeline --workload wan --res 81x512x768 --steps 2   (video: causal video decoder)
 
   pipeline  one request through all three stages on this GPU, the output of each feeding the next
           (prompt tokens -> condition -> T denoising steps -> image): time per stage and its share
@@ -373,9 +374,11 @@ def run_pipeline(args):
     from . import encoder as XE, decoder as XD
     st = Stage(args.workload, args.steps)
     arch = st.arch
-    enc_arch, dec_arch = synth.ENCODERS["t5_xxl"], synth.DECODERS["ae_kl"]
+    video = arch["family"] == "W"            # video latents [C][F][h][w] go to the causal video decoder
+    enc_arch = synth.ENCODERS["t5_xxl"]
+    dec_arch = synth.VIDEO_DECODERS["vae3d"] if video else synth.DECODERS["ae_kl"]
     if arch["cond_dim"] != enc_arch["d_model"] or arch["latent_ch"] != dec_arch["latent_ch"] or arch["patch"][0] != 1:
-        raise SystemExit("pipeline: the workload's condition width / latent channels do not match t5_xxl / ae_kl")
+        raise SystemExit("pipeline: the workload's condition width / latent channels do not match t5_xxl / the decoder")
     specs = args.res.split(",")
     reqs = [[_latent_dims(st.cfg, r) + (st.n_cond,)] for r in specs]
     st.prepare(reqs)
@@ -384,10 +387,13 @@ def run_pipeline(args):
     enc.ensure_workspace(lens)
     enc.init_weights(1, 0.02)
     dec = XD.Decoder(dec_arch)
-    hmax = max(r[0][1] for r in reqs)
-    dec.ensure_workspace(hmax, hmax)
+    big = max(reqs, key=lambda r: dec.workspace_bytes(r[0][1], r[0][2], r[0][0]))[0]
+    if min(dec.workspace_bytes(r[0][1], r[0][2], r[0][0]) for r in reqs) == 0:
+        raise SystemExit("pipeline: a frame size outside the decoder's limits (latent pixels a multiple of 64, of 256 for several frames)")
+    dec.ensure_workspace(big[1], big[2], big[0])
     dec.init_weights(1, 0.02)
     f = dec.up_factor()
+    nominal = st.cfg["steps"]                 # steps of a full request of this workload
     toks = torch.from_numpy(np.concatenate(synth.make_tokens(lens, enc_arch["vocab"]))).cuda()
     cond = torch.empty((st.n_cond, arch["cond_dim"]), dtype=torch.bfloat16, device="cuda")
     sg = np.stack([synth.default_sigmas(args.steps, 1.0)])
@@ -406,28 +412,35 @@ def run_pipeline(args):
     print(f"| image | tokens | encode ms | diffuse ms ({args.steps} steps) | decode ms | total ms | shares E / D / C |", file=sys.stderr)
     print("|---|---|---|---|---|---|---|", file=sys.stderr)
     for spec, rq in zip(specs, reqs):
-        _, h, w, _ = rq[0]
-        n = arch["latent_ch"] * h * w
+        F, h, w, _ = rq[0]
+        n = arch["latent_ch"] * F * h * w
         x0 = torch.from_numpy(synth.gaussian(2, "latent", n).astype(np.float32)).cuda()
         x = x0.clone()
-        img = torch.empty((h * f, w * f, dec_arch["out_ch"]), dtype=torch.float32, device="cuda")
+        img = torch.empty((dec.frames_out(F), h * f, w * f, dec_arch["out_ch"]), dtype=torch.float32, device="cuda")
         st.m.ensure_workspace(rq, args.steps)
         t_e = timed(lambda: enc.forward(lens, toks, cond, None))
 
         def diffuse():
             x.copy_(x0)
             st.m.sample(rq, x, cond, sg)
-        t_d = timed(diffuse)
-        t_c = timed(lambda: dec.forward(h, w, x, img))
+        t_d = timed(diffuse, reps=1 if video else 3)
+        t_c = timed(lambda: dec.forward(h, w, x, img, n=F))
         if not bool(torch.isfinite(img).all().item()):
             raise RuntimeError("non-finite image")
         tot = t_e + t_d + t_c
         row = {"table": "pipeline", "workload": args.workload, "image": spec, "tokens": _tokens(arch, rq[0]),
                "steps": args.steps, "encode_ms": t_e * 1e3, "diffuse_ms": t_d * 1e3, "decode_ms": t_c * 1e3,
                "share_encode": t_e / tot, "share_diffuse": t_d / tot, "share_decode": t_c / tot}
+        if args.steps != nominal:             # the same stage times with the workload's own step count
+            t_n = t_d * nominal / args.steps
+            row.update({"nominal_steps": nominal, "share_encode_nominal": t_e / (t_e + t_n + t_c),
+                        "share_diffuse_nominal": t_n / (t_e + t_n + t_c), "share_decode_nominal": t_c / (t_e + t_n + t_c)})
         print(json.dumps(row), flush=True)
         print(f"| {spec} | {row['tokens']} | {t_e * 1e3:.2f} | {t_d * 1e3:.1f} | {t_c * 1e3:.2f} | {tot * 1e3:.1f} | "
               f"{100 * t_e / tot:.1f} % / {100 * t_d / tot:.1f} % / {100 * t_c / tot:.1f} % |", file=sys.stderr)
+        if args.steps != nominal:
+            print(f"  (at the workload's {nominal} steps, diffuse time scaled from {args.steps}: "
+                  f"{100 * row['share_encode_nominal']:.2f} % / {100 * row['share_diffuse_nominal']:.2f} % / {100 * row['share_decode_nominal']:.2f} %)", file=sys.stderr)
     if args.overlap:
         _overlap(args, specs[-1], reqs[-1])
 
@@ -523,8 +536,8 @@ def main():
         args.res = args.res or ("256x384,512x768" if args.decoder.startswith("vae3d") else "128,256,512,1024")
         return run_decode(args)
     if args.table == "pipeline":
-        args.res = args.res or "512,1024"
-        args.steps = args.steps or 28
+        args.res = args.res or ("81x512x768" if args.workload == "wan" else "512,1024")
+        args.steps = args.steps or (2 if args.workload == "wan" else 28)
         return run_pipeline(args)
     if args.res is None:
         args.res = DEFAULT_RES.get((args.table, args.workload))
