@@ -48,13 +48,15 @@ dit_status dec_create(const dec_config* cfg, int device, void* hip_stream, dec_c
 void       dec_destroy(dec_ctx* ctx);
 const char* dec_last_error(const dec_ctx* ctx);
 
-/* Bytes of the weight arena and of the workspace for n latents of h x w (0 for an invalid size:
- * h, w >= 1 and (h*w) % 64 == 0 so that the mid-block attention product has whole k-slabs;
- * 1 <= n <= 128 and, for n > 1, (h*w) % 256 == 0 so that no group-norm chunk straddles images). */
-/* A video decoder takes n = the latent frames of ONE video in every call below; the limits then
- * apply to its output frames, dec_frames_out(ctx, n) (n for an image decoder; 0 for n < 1), of which
- * there may be at most 128. */
+/* A video decoder takes n = the latent frames of ONE video in every call below and produces
+ * dec_frames_out(ctx, n) frames (an image decoder: n images; 0 for n < 1). */
 int    dec_frames_out(const dec_ctx* ctx, int n);
+/* Bytes of the weight arena and of the workspace for n latents of h x w.  0 for an invalid size:
+ * h, w in 1..4096, (h*w) % 64 == 0 (whole k-slabs in the mid-block attention product) and
+ * h*w <= 65536 (the score matrix is held whole); at most 128 images or output frames and,
+ * with more than one, (h*w) % 256 == 0 (no group-norm chunk straddles images); fewer than 2^29
+ * output pixels in all; one bordered image of the widest level (three of them for a video)
+ * below 2^31 elements. */
 size_t dec_weight_bytes(const dec_ctx* ctx);
 size_t dec_workspace_bytes(const dec_ctx* ctx, int n, int h, int w);
 dit_status dec_bind(dec_ctx* ctx, void* dev_weights, size_t weight_bytes, void* dev_workspace,
