@@ -141,6 +141,8 @@ def run_workload(name, K, W, calibrate=False):
     ew = {}
     for k in ("ln_modulate", "qknorm_rope_vt", "update"):
         p = prof[k]
+        if p["ms"] <= 0:          # class without a launch in this step (q/k norm, rotary code and V^T run in the QKV epilogue)
+            continue
         ew[k] = {"ms_per_step": p["ms"] / K, "GBps": p["bytes"] / p["ms"] / 1e6 if p["ms"] > 0 else 0.0,
                  "frac_hbm": (p["bytes"] / p["ms"] / 1e6) / PEAK_HBM_GBS if p["ms"] > 0 else 0.0}
     return {
