@@ -521,8 +521,12 @@ dit_status dec_forward(dec_ctx* c, int n, int h, int w, const float* latent, flo
   F.gn("out.gn", x, F.frame(H, W, prev), H, W, prev, 1, 1);
   {
     const DTensor* to = find(c, "conv_out.w");
-    // (the small-output kernel knows the 9-tap form only; 27 taps and wide last levels go through the product)
-    if (g.temporal || !launch_conv3_small(s, img, Wm(c, "conv_out.w"), to->ld, Wv(c, "conv_out.b"), image, H, W, to->cin_pad, g.out_ch, n)) {
+    // 27 taps: the 9-tap kernel once per frame tap kf, on the stack shifted by kf frames, adding up in that order
+    bool direct = true;
+    for (int kf = 0; kf < F.kt && direct; ++kf)
+      direct = launch_conv3_small(s, img + (size_t)kf * (H + 2) * (W + 2) * to->cin_pad, Wm(c, "conv_out.w") + (size_t)kf * 9 * to->cin_pad,
+                                  to->ld, kf == 0 ? Wv(c, "conv_out.b") : nullptr, image, H, W, to->cin_pad, g.out_ch, F.B, kf > 0);
+    if (!direct) {
       F.conv3("conv_out", img, H, W, OUT_F32, F.at<float>(L.out4), 4, false);     // as a product, rows 4 wide, then compacted
       launch_compact_rows(s, F.at<float>(L.out4), 4, image, (long long)F.B * H * W, g.out_ch);
     }

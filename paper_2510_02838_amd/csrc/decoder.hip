@@ -337,7 +337,7 @@ void launch_softmax_rows(hipStream_t s, const float* sc, int lds_, bf16_t* out, 
 template <int OC>
 __global__ __launch_bounds__(256) void conv3_small_kernel(const bf16_t* __restrict__ img, const bf16_t* __restrict__ w, int ldw,
                                                           const float* __restrict__ bias, float* __restrict__ out,
-                                                          int H, int W, int C, int lsh, int B) {
+                                                          int H, int W, int C, int lsh, int B, int accumulate) {
   typedef __bf16 bf2 __attribute__((ext_vector_type(2)));
   const int lane = threadIdx.x & 63;
   const int lpp = 1 << lsh;                         // lanes per pixel = C / 8
@@ -379,12 +379,12 @@ __global__ __launch_bounds__(256) void conv3_small_kernel(const bf16_t* __restri
       for (int o = 0; o < OC; ++o) acc[o] += __shfl_xor(acc[o], off);
     if (ok && sub == 0) {
 #pragma unroll
-      for (int o = 0; o < OC; ++o) out[p * OC + o] = acc[o] + (bias ? bias[o] : 0.f);
+      for (int o = 0; o < OC; ++o) out[p * OC + o] = (accumulate ? out[p * OC + o] : 0.f) + acc[o] + (bias ? bias[o] : 0.f);
     }
   }
 }
 bool launch_conv3_small(hipStream_t s, const bf16_t* img, const bf16_t* w, int ldw, const float* bias, float* out,
-                        int H, int W, int C, int OC, int B) {
+                        int H, int W, int C, int OC, int B, int accumulate) {
   if (OC < 1 || OC > 4 || (C != 64 && C != 128 && C != 256 && C != 512)) return false;
   const long long P = (long long)H * W * B;
   if (P == 0) return true;
@@ -394,10 +394,10 @@ bool launch_conv3_small(hipStream_t s, const bf16_t* img, const bf16_t* w, int l
   const long long want = (groups + 3) / 4;
   dim3 g((unsigned)(want < 4096 ? want : 4096)), b(256);
   switch (OC) {
-    case 1: hipLaunchKernelGGL(conv3_small_kernel<1>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B); break;
-    case 2: hipLaunchKernelGGL(conv3_small_kernel<2>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B); break;
-    case 3: hipLaunchKernelGGL(conv3_small_kernel<3>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B); break;
-    default: hipLaunchKernelGGL(conv3_small_kernel<4>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B); break;
+    case 1: hipLaunchKernelGGL(conv3_small_kernel<1>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B, accumulate); break;
+    case 2: hipLaunchKernelGGL(conv3_small_kernel<2>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B, accumulate); break;
+    case 3: hipLaunchKernelGGL(conv3_small_kernel<3>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B, accumulate); break;
+    default: hipLaunchKernelGGL(conv3_small_kernel<4>, g, b, 0, s, img, w, ldw, bias, out, H, W, C, lsh, B, accumulate); break;
   }
   return true;
 }

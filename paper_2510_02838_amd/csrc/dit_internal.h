@@ -203,9 +203,10 @@ void launch_cast_bf16(hipStream_t s, const float* x, bf16_t* out, long long n); 
 // out[r][j] = softmax_j(sc[r][j] * scale) as bf16, j < n; columns n..ldo-1 are set to zero
 void launch_softmax_rows(hipStream_t s, const float* sc, int lds_, bf16_t* out, int ldo, int rows, int n, float scale_log2);
 // 3x3 convolution of a bordered bf16 image to OC <= 4 fp32 channels without the matrix cores;
-// false (nothing launched) if the shape is outside its limits (C in {64,128,256,512}, OC <= 4)
+// false (nothing launched) if the shape is outside its limits (C in {64,128,256,512}, OC <= 4).
+// accumulate: out += instead of out = (one launch per frame tap of a 3x3x3 convolution).
 bool launch_conv3_small(hipStream_t s, const bf16_t* img, const bf16_t* w, int ldw, const float* bias, float* out,
-                        int H, int W, int C, int OC, int B = 1);
+                        int H, int W, int C, int OC, int B = 1, int accumulate = 0);
 void launch_compact_rows(hipStream_t s, const float* src, int lds_, float* dst, long long P, int C);
 
 // weights
