@@ -155,35 +155,49 @@ __global__ __launch_bounds__(64) void gn_combine_kernel(const double2* __restric
   stats[g] = make_float2((float)mean, (float)(1.0 / sqrt(var + 1e-6)));
 }
 // pass 3: y = (x - mean_g) rstd_g gamma_c + beta_c, optional SiLU, bf16, bordered or plain rows.
-// One image row per blockIdx.y; a thread takes 8 consecutive channels of one pixel.
+// One image row per blockIdx.y; a thread takes 8 consecutive channels of four consecutive pixels (gain, bias and
+// the group statistics are fetched once for the four, and the four pixels' loads are in flight together).
 __global__ __launch_bounds__(256) void gn_apply_kernel(const float* __restrict__ x, const float2* __restrict__ stats,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        bf16_t* __restrict__ out, int W, int C, int osh, int gsh,
                                                        int silu, int pad, int groups) {
-  const int i = blockIdx.x * 256 + threadIdx.x;      // unit of 8 channels inside the row
+  const int i = blockIdx.x * 256 + threadIdx.x;      // unit: 8 channels of a group of four pixels of the row
   const int opc = C >> 3;                            // = 1 << osh
-  if (i >= W * opc) return;
+  if (i >= ((W + 3) >> 2) * opc) return;
   const int H = gridDim.y, img = blockIdx.z;         // one image per blockIdx.z
   x += (size_t)img * H * W * C;
   out += (size_t)img * (pad ? (size_t)(H + 2) * (W + 2) : (size_t)H * W) * C;
   stats += img * groups;
-  const int y = blockIdx.y, xx = i >> osh, c = (i & (opc - 1)) * 8;
-  const float* xr = x + ((size_t)y * W + xx) * C + c;
-  const float4 v0 = *(const float4*)xr, v1 = *(const float4*)(xr + 4);
+  const int y = blockIdx.y, x0 = (i >> osh) * 4, c = (i & (opc - 1)) * 8;
+  const float* xr = x + ((size_t)y * W + x0) * C + c;
+  float4 v0[4], v1[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (x0 + k < W) { v0[k] = *(const float4*)(xr + (size_t)k * C); v1[k] = *(const float4*)(xr + (size_t)k * C + 4); }
   const float4 g0 = *(const float4*)(gamma + c), g1 = *(const float4*)(gamma + c + 4);
   const float4 b0 = *(const float4*)(beta + c), b1 = *(const float4*)(beta + c + 4);
-  float r[8] = {v0.x, v0.y, v0.z, v0.w, v1.x, v1.y, v1.z, v1.w};
   const float gg[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
   const float bb[8] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w};
+  float sc[8], sh[8];                                // y = x * sc + sh
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     const float2 st = stats[(c + j) >> gsh];
-    r[j] = (r[j] - st.x) * st.y * gg[j] + bb[j];
-    if (silu) r[j] = d_silu(r[j]);
+    sc[j] = st.y * gg[j];
+    sh[j] = bb[j] - st.x * sc[j];
   }
-  uint4 w;
-  w.x = d_pack2(r[0], r[1]); w.y = d_pack2(r[2], r[3]); w.z = d_pack2(r[4], r[5]); w.w = d_pack2(r[6], r[7]);
-  *(uint4*)(out + dst_pixel(y, xx, W, pad) * C + c) = w;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    if (x0 + k >= W) break;
+    float r[8] = {v0[k].x, v0[k].y, v0[k].z, v0[k].w, v1[k].x, v1[k].y, v1[k].z, v1[k].w};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      r[j] = r[j] * sc[j] + sh[j];
+      if (silu) r[j] = d_silu(r[j]);
+    }
+    uint4 w;
+    w.x = d_pack2(r[0], r[1]); w.y = d_pack2(r[2], r[3]); w.z = d_pack2(r[4], r[5]); w.w = d_pack2(r[6], r[7]);
+    *(uint4*)(out + dst_pixel(y, x0 + k, W, pad) * C + c) = w;
+  }
 }
 
 // B images of H x W; statistics per image and group.  ready_chunks > 0: `partial` already holds
@@ -210,7 +224,7 @@ void launch_group_norm(hipStream_t s, const float* x, const float* gamma, const 
   double2* part = (double2*)((unsigned char*)stats + GN_STATS_HEAD);
   hipLaunchKernelGGL(gn_finalize_kernel, dim3(groups, shares, B), dim3(256), 0, s, partial, stats, part, chunks, C, groups, P);
   if (shares > 1) hipLaunchKernelGGL(gn_combine_kernel, dim3(B), dim3(64), 0, s, part, stats, shares, C / groups, groups, P);
-  const int units = W * (C >> 3);
+  const int units = ((W + 3) >> 2) * (C >> 3);
   hipLaunchKernelGGL(gn_apply_kernel, dim3((units + 255) / 256, H, B), dim3(256), 0, s, x, stats, gamma, beta, out, W, C, csh - 3, gsh, silu, pad, groups);
 }
 size_t group_norm_partial_bytes(long long pixels, int C) {
