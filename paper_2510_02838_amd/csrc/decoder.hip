@@ -231,39 +231,52 @@ size_t group_norm_partial_bytes(long long pixels, int C) {
   return (size_t)((pixels + GN_CHUNK - 1) / GN_CHUNK) * C * 2 * sizeof(float);
 }
 
-// nearest 2x upsampling of the fp32 stream into a bf16 bordered image: out pixel (y, x) = in (y/2, x/2)
+// nearest 2x upsampling of the fp32 stream into a bf16 bordered image: out pixel (y, x) = in (y/2, x/2).
+// A thread reads 8 channels of one input pixel once and writes the four output pixels that show it.
 __global__ __launch_bounds__(256) void upsample_pad_kernel(const float* __restrict__ x, bf16_t* __restrict__ out,
                                                            int H, int W, int C, int frame_up) {       // H, W: input size
   const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  const int qpc = C >> 2;
-  const int H2 = 2 * H, W2 = 2 * W;
-  if (i >= (long long)H2 * W2 * qpc) return;
+  const int opc = C >> 3;
+  const int W2 = 2 * W;
+  if (i >= (long long)H * W * opc) return;
   x += (size_t)(frame_up ? (blockIdx.y + 1) >> 1 : blockIdx.y) * H * W * C;     // one output image per blockIdx.y
-  out += (size_t)blockIdx.y * (H2 + 2) * (W2 + 2) * C;
-  const long long p = i / qpc;
-  const int c = (int)(i % qpc) * 4;
-  const int y = (int)(p / W2), xx = (int)(p % W2);
-  const float4 v = ((const float4*)(x + ((long long)(y >> 1) * W + (xx >> 1)) * C))[c >> 2];
-  uint2 w;
-  w.x = d_pack2(v.x, v.y); w.y = d_pack2(v.z, v.w);
-  *(uint2*)(out + dst_pixel(y, xx, W2, 1) * C + c) = w;
+  out += (size_t)blockIdx.y * (2 * H + 2) * (W2 + 2) * C;
+  const long long p = i / opc;
+  const int c = (int)(i % opc) * 8;
+  const int y = (int)(p / W), xx = (int)(p % W);
+  const float4* src = (const float4*)(x + p * C + c);
+  const float4 v0 = src[0], v1 = src[1];
+  uint4 w;
+  w.x = d_pack2(v0.x, v0.y); w.y = d_pack2(v0.z, v0.w); w.z = d_pack2(v1.x, v1.y); w.w = d_pack2(v1.z, v1.w);
+#pragma unroll
+  for (int dy = 0; dy < 2; ++dy)
+#pragma unroll
+    for (int dx = 0; dx < 2; ++dx)
+      *(uint4*)(out + dst_pixel(2 * y + dy, 2 * xx + dx, W2, 1) * C + c) = w;
 }
 void launch_upsample_pad(hipStream_t s, const float* x, bf16_t* out, int H, int W, int C, int B, int frame_up) {
-  const long long n = (long long)4 * H * W * (C / 4);
+  const long long n = (long long)H * W * (C / 8);
   if (n && B) hipLaunchKernelGGL(upsample_pad_kernel, dim3((unsigned)((n + 255) / 256), B), dim3(256), 0, s, x, out, H, W, C, frame_up);
 }
 
 // fp32 -> bf16, 4 elements per thread (plain rows)
+// (a workgroup takes 4 x 256 float4s, a thread one of each quarter: four loads in flight per thread)
 __global__ __launch_bounds__(256) void cast_bf16_kernel(const float* __restrict__ x, bf16_t* __restrict__ out, long long n4) {
-  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
-  if (i >= n4) return;
-  const float4 v = ((const float4*)x)[i];
-  uint2 w;
-  w.x = d_pack2(v.x, v.y); w.y = d_pack2(v.z, v.w);
-  ((uint2*)out)[i] = w;
+  const long long i0 = (long long)blockIdx.x * 1024 + threadIdx.x;
+  float4 v[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k)
+    if (i0 + k * 256 < n4) v[k] = ((const float4*)x)[i0 + k * 256];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    if (i0 + k * 256 >= n4) break;
+    uint2 w;
+    w.x = d_pack2(v[k].x, v[k].y); w.y = d_pack2(v[k].z, v[k].w);
+    ((uint2*)out)[i0 + k * 256] = w;
+  }
 }
 void launch_cast_bf16(hipStream_t s, const float* x, bf16_t* out, long long n) {
-  if (n) hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)((n / 4 + 255) / 256)), dim3(256), 0, s, x, out, n / 4);
+  if (n) hipLaunchKernelGGL(cast_bf16_kernel, dim3((unsigned)((n / 4 + 1023) / 1024)), dim3(256), 0, s, x, out, n / 4);
 }
 
 // row softmax of fp32 scores times `scale`, written as bf16 with row stride ldo; columns from n to
